@@ -1,0 +1,69 @@
+"""The five benchmark workloads as named presets (shapes only; all tensors are synthetic).
+
+Shapes follow the attention geometry of the two 7-8B reasoning models the paper
+evaluates (Sec. 6.1): 32 query / 8 KV heads (Llama-3-8B-shaped) and 28 query /
+4 KV heads (Qwen2.5-7B-shaped), head_dim 128, decode lengths up to 16k-32k.
+`budget`, `window`, `evict_every` are the selection-window size kept after a
+trigger, the local-window size and the trigger period (Sec. 4.2).
+"""
+from dataclasses import dataclass, replace
+from typing import Tuple
+
+
+@dataclass(frozen=True)
+class Workload:
+    name: str
+    n_layers: int
+    batch: int
+    n_q_heads: int
+    n_kv_heads: int
+    head_dim: int
+    prompt: int                 # M, question-window length (same for every sequence)
+    steps: Tuple[int, int]      # decode steps per sequence, uniform in [lo, hi]
+    budget: int
+    window: int
+    evict_every: int
+    plant: Tuple[float, float]  # fraction of planted critical keys, first..last layer
+    k_dist: str = "normal"      # "normal" | "student_t3"
+    external_scores: bool = False
+    seed: int = 0xD7A50000
+
+    @property
+    def capacity(self) -> int:
+        return self.prompt + self.budget + self.window + self.evict_every
+
+    @property
+    def group(self) -> int:
+        return self.n_q_heads // self.n_kv_heads
+
+    @property
+    def steady_len(self) -> int:
+        """Cache length right after a trigger in steady state."""
+        return self.prompt + self.budget + self.window
+
+    def plant_fraction(self, layer: int) -> float:
+        lo, hi = self.plant
+        if self.n_layers <= 1:
+            return lo
+        return lo + (hi - lo) * layer / (self.n_layers - 1)
+
+
+CONFIGS = {
+    "cfg1": Workload("cfg1", 1, 1, 8, 2, 64, 64, (512, 512), 128, 32, 16, (0.03, 0.03),
+                     seed=0xD7A50001),
+    "cfg2": Workload("cfg2", 1, 1, 32, 8, 128, 256, (16384, 16384), 4096, 128, 64, (0.02, 0.02),
+                     seed=0xD7A50002),
+    "cfg3": Workload("cfg3", 1, 32, 28, 4, 128, 256, (4096, 32768), 2048, 128, 64, (0.02, 0.02),
+                     seed=0xD7A50003),
+    "cfg4": Workload("cfg4", 32, 64, 32, 8, 128, 512, (8192, 8192), 2048, 64, 32, (0.01, 0.05),
+                     seed=0xD7A50004),
+    "cfg5": Workload("cfg5", 28, 128, 28, 4, 128, 128, (1024, 32768), 1024, 32, 16, (0.0, 0.0),
+                     k_dist="student_t3", seed=0xD7A50005),
+}
+# Same streams as cfg5, scores supplied from outside on a 64-level grid so that
+# every trigger has exact ties at the cut.
+CONFIGS["cfg5b"] = replace(CONFIGS["cfg5"], name="cfg5b", external_scores=True)
+
+
+def get(name: str) -> Workload:
+    return CONFIGS[name]
