@@ -1,0 +1,168 @@
+/*
+ * dynts.h -- C ABI of the MI355X (gfx950) DynTS decode hot path.
+ *
+ * DynTS (Dynamic Thinking-Token Selection) decodes over a budget-bounded KV cache: per
+ * layer the cache of a sequence is the question window (M prompt slots, never evicted),
+ * the selection window and the local window (Sec. 4.2).  Every decode step attends over
+ * the retained slots (Eq. attn-score, Eq. attn-o), every cached thinking token carries an
+ * importance score (Eq. importance-score, kept here in running form per layer and KV
+ * head), and on a trigger the top-k thinking tokens of the selection window are kept and
+ * the rest evicted.
+ *
+ * Conventions
+ *  - All array arguments are DEVICE pointers unless a comment says "host".  The caller
+ *    owns every buffer; the context owns host metadata only and never allocates device
+ *    memory.  bf16 arrays are passed as uint16_t (raw bits).
+ *  - Every call enqueues its kernels on the caller's stream (a hipStream_t passed as
+ *    void*, NULL = the null stream) and returns without synchronising the host.  Calls on
+ *    one context must be stream-ordered with respect to each other.
+ *  - Return value: DYNTS_OK or a negative error.  Argument errors are found on the host
+ *    before anything is launched.  Conditions only the device can see (a sequence that
+ *    would overflow `capacity`) are latched into the bound `status` word: bit 0 = an
+ *    append was dropped because the cache was full.
+ *  - Layout (C order, L = n_layers, Nb = batch, Hkv = n_kv_heads, cap = capacity, d = head_dim):
+ *      K, V      bf16  [L][Nb][Hkv][cap][d]   rows in position order
+ *      S         fp32  [L][Nb][Hkv][cap]      importance score; +inf on question slots
+ *      pos       int32 [L][Nb][Hkv][cap]      original token position of each slot
+ *      seq_len   int32 [L][Nb]                slots in use (equal for all KV heads)
+ *      next_pos  int32 [L][Nb]                position the next appended token receives
+ *      n_prompt  int32 [Nb]                   M of each sequence
+ *  - Query head hq reads KV head hq / G, G = n_q_heads / n_kv_heads (grouped-query
+ *    attention, Sec. 2 "Attention Mechanism").  Supported: head_dim 64 or 128, G <= 16.
+ *  - `active` (uint8 [Nb], may be NULL = all active) masks finished sequences of a ragged
+ *    batch: nothing is appended, attended or written for them.
+ */
+#ifndef DYNTS_H
+#define DYNTS_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define DYNTS_OK 0
+#define DYNTS_EINVAL (-1)     /* a value outside its documented range */
+#define DYNTS_ENULL (-2)      /* a required pointer is NULL */
+#define DYNTS_ESHAPE (-3)     /* unsupported shape: head_dim, group size, divisibility */
+#define DYNTS_ECAPACITY (-4)  /* capacity < budget + window + evict_every, or an index stride too small */
+#define DYNTS_ENOTBOUND (-5)  /* dynts_bind has not been called */
+#define DYNTS_EWORKSPACE (-6) /* workspace smaller than dynts_workspace_bytes, or misaligned */
+#define DYNTS_EHIP (-7)       /* the HIP runtime refused a launch */
+#define DYNTS_EPENDING (-8)   /* rows would move while a score update is still deferred */
+
+#define DYNTS_SCORE_ACCUMULATE 0 /* score = attention received so far (Eq. importance-score) */
+#define DYNTS_SCORE_EXTERNAL 1   /* score supplied at append (the predictor's output, Sec. 4.1) */
+
+typedef struct dynts_config {
+  int32_t n_layers;
+  int32_t batch;
+  int32_t n_q_heads;
+  int32_t n_kv_heads;
+  int32_t head_dim;
+  int32_t capacity;     /* cap: slots per (sequence, KV head); >= prompt + budget + window + evict_every */
+  int32_t budget;       /* selection-window slots kept by a trigger (the k of top-k, default k_keep) */
+  int32_t window;       /* local-window slots, always kept */
+  int32_t evict_every;  /* trigger period in steps = eviction volume K of Sec. 5 */
+  float softmax_scale;  /* 0 => 1/sqrt(head_dim) (Eq. attn-score) */
+  int32_t score_mode;   /* DYNTS_SCORE_* */
+} dynts_config;
+
+typedef struct dynts_ctx dynts_ctx;
+
+/* Library version, major*10000 + minor*100 + patch. */
+int dynts_version(void);
+/* Static text for an error code. */
+const char *dynts_strerror(int code);
+
+/* Validate `cfg` and make a host-side context.  No device work, no HIP call. */
+int dynts_create(const dynts_config *cfg, dynts_ctx **out);
+int dynts_destroy(dynts_ctx *ctx);
+
+/* Bytes of device scratch the kernels need for `cfg` (split partials, the saved query and
+ * softmax statistics of the deferred score update).  0 if cfg is invalid. */
+size_t dynts_workspace_bytes(const dynts_config *cfg);
+
+/* Attach the caller's device buffers (layout above).  `workspace` must be 256-byte aligned
+ * and zero-filled once by the caller before first use; `status` is one int32, zeroed by
+ * the caller.  Binding resets the context's deferred-update bookkeeping. */
+int dynts_bind(dynts_ctx *ctx, uint16_t *K, uint16_t *V, float *S, int32_t *pos,
+               int32_t *seq_len, int32_t *next_pos, int32_t *n_prompt, void *workspace,
+               size_t workspace_bytes, int32_t *status);
+
+/* Question window (Sec. 4.2, first paragraph): copy the prompt rows of one layer,
+ * K0, V0 bf16 [Nb][Hkv][m_max][d], m int32 [Nb] with m[b] <= m_max, into slots [0, m[b]);
+ * scores +inf, pos = slot, seq_len = next_pos = n_prompt = m. */
+int dynts_prefill(dynts_ctx *ctx, int32_t layer, const uint16_t *K0, const uint16_t *V0,
+                  int32_t m_max, const int32_t *m, void *stream);
+
+/* Append the current token (Sec. 4.2, second paragraph): k_new, v_new bf16 [Nb][Hkv][d] go
+ * to slot seq_len[b] of every KV head; score 0, or s_new fp32 [Nb][Hkv] when score_mode is
+ * DYNTS_SCORE_EXTERNAL (then s_new is required); pos = next_pos++; seq_len++. */
+int dynts_append(dynts_ctx *ctx, int32_t layer, const uint16_t *k_new, const uint16_t *v_new,
+                 const float *s_new, const uint8_t *active, void *stream);
+
+/* Decode attention (Eq. attn-score, Eq. attn-o): for each active sequence and query head,
+ * out[b][hq][:] = sum_j softmax_j(q.k_j * scale) v_j over slots [0, seq_len[b]).
+ * q bf16 [Nb][Hq][d]; out fp32 [Nb][Hq][d]; lse fp32 [Nb][Hq] (may be NULL) receives
+ * log sum_j exp(logit_j).  Leaves what dynts_update_scores needs in the workspace. */
+int dynts_decode_attend(dynts_ctx *ctx, int32_t layer, const uint16_t *q, const uint8_t *active,
+                        float *out, float *lse, void *stream);
+
+/* Score accumulation (Eq. importance-score in running form; App. B.1 sums over heads):
+ * S[b][h][j] += sum over the G heads of the group of alpha[g][j], for every thinking slot
+ * j >= n_prompt[b] the last attend call of this layer saw.  A no-op when nothing is
+ * outstanding or score_mode is external. */
+int dynts_update_scores(dynts_ctx *ctx, int32_t layer, void *stream);
+
+/* dynts_decode_attend with the score accumulation fused into the same pass over K: the
+ * accumulation owed by the PREVIOUS attend call of this layer is applied while this call
+ * streams the cache, and this call's own accumulation becomes the outstanding one.  S
+ * therefore lags by one step until dynts_update_scores (or dynts_select_evict, which
+ * applies it first) is called. */
+int dynts_decode_attend_update(dynts_ctx *ctx, int32_t layer, const uint16_t *q,
+                               const uint8_t *active, float *out, float *lse, void *stream);
+
+/* One whole decode step of a layer in one pass: dynts_append + dynts_decode_attend_update. */
+int dynts_decode_step(dynts_ctx *ctx, int32_t layer, const uint16_t *q, const uint16_t *k_new,
+                      const uint16_t *v_new, const float *s_new, const uint8_t *active,
+                      float *out, float *lse, void *stream);
+
+/* KV-cache selection (Sec. 4.2, third paragraph): for every sequence with trigger[b] != 0
+ * (uint8 [Nb], NULL = all) and every KV head keep all question slots, the last `window`
+ * slots, and of the slots between them the k_keep with the highest score (ties: lower
+ * position first).  keep_idx int32 [Nb][Hkv][keep_stride] receives the retained slots in
+ * ascending order, new_len int32 [Nb] their count (seq_len[b] where not triggered or when
+ * the selection window holds <= k_keep slots).  k_keep < 0 means cfg.budget.  Applies an
+ * outstanding score accumulation first.  NaN scores give an unspecified (in-bounds) choice. */
+int dynts_select_evict(dynts_ctx *ctx, int32_t layer, const uint8_t *trigger, int32_t k_keep,
+                       int32_t *keep_idx, int32_t keep_stride, int32_t *new_len, void *stream);
+
+/* Eviction (Sec. 4.2): stable in-place gather of the K, V, S and pos rows listed in
+ * keep_idx to slots [0, new_len[b]) and seq_len[b] = new_len[b], for triggered sequences.
+ * keep_idx rows must be strictly ascending and < seq_len[b] (indices are clamped into the
+ * cache, never followed out of bounds).  DYNTS_EPENDING if a score accumulation is
+ * outstanding for this layer. */
+int dynts_compact(dynts_ctx *ctx, int32_t layer, const uint8_t *trigger, const int32_t *keep_idx,
+                  int32_t keep_stride, const int32_t *new_len, void *stream);
+
+/* Native decode loop: enqueue n_steps whole steps of every layer without returning to the
+ * caller -- per step and layer dynts_decode_step, and on steps with evict_steps[i] != 0
+ * (host uint8 [n_steps]) dynts_select_evict(k_keep = budget) + dynts_compact for the
+ * sequences flagged in trigger (device uint8 [n_steps][Nb], NULL = all).
+ *   q      bf16 [n_steps][L][Nb][Hq][d]      k_new, v_new bf16 [n_steps][L][Nb][Hkv][d]
+ *   s_new  fp32 [n_steps][Nb][Hkv] (external mode, same score for every layer) or NULL
+ *   active uint8 [n_steps][Nb] or NULL
+ *   out    fp32 [L][Nb][Hq][d], overwritten every step (out_step_stride = 0) or one slab
+ *          per step (out_step_stride = L*Nb*Hq*d elements)
+ *   keep_idx int32 [Nb][Hkv][cap], new_len int32 [Nb]: scratch for the triggers. */
+int dynts_decode_loop(dynts_ctx *ctx, int32_t n_steps, const uint16_t *q, const uint16_t *k_new,
+                      const uint16_t *v_new, const float *s_new, const uint8_t *active,
+                      const uint8_t *evict_steps, const uint8_t *trigger, float *out,
+                      size_t out_step_stride, int32_t *keep_idx, int32_t *new_len, void *stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* DYNTS_H */

@@ -1,0 +1,229 @@
+"""ctypes binding of libdynts.so: the same names as include/dynts.h, argument marshalling only.
+
+PyTorch is used for device memory and streams; every step of the decode path runs in the
+library's kernels.  There is no fallback: if the library is missing, import of this module
+raises.
+"""
+import ctypes as C
+import os
+
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libdynts.so")
+
+DYNTS_OK = 0
+DYNTS_EINVAL, DYNTS_ENULL, DYNTS_ESHAPE, DYNTS_ECAPACITY = -1, -2, -3, -4
+DYNTS_ENOTBOUND, DYNTS_EWORKSPACE, DYNTS_EHIP, DYNTS_EPENDING = -5, -6, -7, -8
+DYNTS_SCORE_ACCUMULATE, DYNTS_SCORE_EXTERNAL = 0, 1
+
+EXPORTS = [
+    "dynts_version", "dynts_strerror", "dynts_create", "dynts_destroy", "dynts_workspace_bytes",
+    "dynts_bind", "dynts_prefill", "dynts_append", "dynts_decode_attend", "dynts_update_scores",
+    "dynts_decode_attend_update", "dynts_decode_step", "dynts_select_evict", "dynts_compact",
+    "dynts_decode_loop",
+]
+
+
+class dynts_config(C.Structure):
+    _fields_ = [("n_layers", C.c_int32), ("batch", C.c_int32), ("n_q_heads", C.c_int32),
+                ("n_kv_heads", C.c_int32), ("head_dim", C.c_int32), ("capacity", C.c_int32),
+                ("budget", C.c_int32), ("window", C.c_int32), ("evict_every", C.c_int32),
+                ("softmax_scale", C.c_float), ("score_mode", C.c_int32)]
+
+
+def _load():
+    if not os.path.exists(LIB_PATH):
+        raise ImportError(
+            "%s is missing: build it with `python -m paper_2601_18383_amd.build` "
+            "(there is no CPU fallback for the decode path)" % LIB_PATH)
+    lib = C.CDLL(LIB_PATH)
+    vp, i32, sz = C.c_void_p, C.c_int32, C.c_size_t
+    lib.dynts_version.restype = C.c_int
+    lib.dynts_strerror.restype = C.c_char_p
+    lib.dynts_strerror.argtypes = [C.c_int]
+    lib.dynts_create.argtypes = [C.POINTER(dynts_config), C.POINTER(vp)]
+    lib.dynts_destroy.argtypes = [vp]
+    lib.dynts_workspace_bytes.restype = sz
+    lib.dynts_workspace_bytes.argtypes = [C.POINTER(dynts_config)]
+    lib.dynts_bind.argtypes = [vp] * 9 + [sz, vp]
+    lib.dynts_prefill.argtypes = [vp, i32, vp, vp, i32, vp, vp]
+    lib.dynts_append.argtypes = [vp, i32, vp, vp, vp, vp, vp]
+    lib.dynts_decode_attend.argtypes = [vp, i32, vp, vp, vp, vp, vp]
+    lib.dynts_update_scores.argtypes = [vp, i32, vp]
+    lib.dynts_decode_attend_update.argtypes = [vp, i32, vp, vp, vp, vp, vp]
+    lib.dynts_decode_step.argtypes = [vp, i32, vp, vp, vp, vp, vp, vp, vp, vp]
+    lib.dynts_select_evict.argtypes = [vp, i32, vp, i32, vp, i32, vp, vp]
+    lib.dynts_compact.argtypes = [vp, i32, vp, vp, i32, vp, vp]
+    lib.dynts_decode_loop.argtypes = [vp, i32, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp, vp, vp]
+    for name in EXPORTS:
+        getattr(lib, name)
+    return lib
+
+
+lib = _load()
+
+
+class DyntsError(RuntimeError):
+    def __init__(self, code, where):
+        self.code = code
+        super().__init__("%s: %s (%d)" % (where, lib.dynts_strerror(code).decode(), code))
+
+
+def _ptr(t, dtype=None):
+    """Device (or host) address of a tensor, None -> NULL."""
+    if t is None:
+        return None
+    if isinstance(t, int):
+        return t
+    assert t.is_contiguous(), "tensors crossing the C ABI must be contiguous"
+    if dtype is not None:
+        assert t.dtype == dtype, "expected %s, got %s" % (dtype, t.dtype)
+    return t.data_ptr()
+
+
+def _stream(stream):
+    if stream is None:
+        return torch.cuda.current_stream().cuda_stream
+    if isinstance(stream, int):
+        return stream
+    return stream.cuda_stream
+
+
+def _check(rc, where):
+    if rc != DYNTS_OK:
+        raise DyntsError(rc, where)
+
+
+def dynts_version():
+    return int(lib.dynts_version())
+
+
+def dynts_strerror(code):
+    return lib.dynts_strerror(int(code)).decode()
+
+
+def make_config(n_layers, batch, n_q_heads, n_kv_heads, head_dim, capacity, budget, window, evict_every,
+                softmax_scale=0.0, score_mode=DYNTS_SCORE_ACCUMULATE):
+    return dynts_config(n_layers, batch, n_q_heads, n_kv_heads, head_dim, capacity, budget, window,
+                        evict_every, softmax_scale, score_mode)
+
+
+def dynts_create(cfg):
+    ctx = C.c_void_p()
+    _check(lib.dynts_create(C.byref(cfg), C.byref(ctx)), "dynts_create")
+    return ctx
+
+
+def dynts_destroy(ctx):
+    _check(lib.dynts_destroy(ctx), "dynts_destroy")
+
+
+def dynts_workspace_bytes(cfg):
+    return int(lib.dynts_workspace_bytes(C.byref(cfg)))
+
+
+def dynts_bind(ctx, K, V, S, pos, seq_len, next_pos, n_prompt, workspace, status):
+    _check(lib.dynts_bind(ctx, _ptr(K, torch.bfloat16), _ptr(V, torch.bfloat16), _ptr(S, torch.float32),
+                          _ptr(pos, torch.int32), _ptr(seq_len, torch.int32), _ptr(next_pos, torch.int32),
+                          _ptr(n_prompt, torch.int32), _ptr(workspace), workspace.numel() * workspace.element_size(),
+                          _ptr(status, torch.int32)), "dynts_bind")
+
+
+def dynts_prefill(ctx, layer, K0, V0, m, stream=None):
+    _check(lib.dynts_prefill(ctx, layer, _ptr(K0, torch.bfloat16), _ptr(V0, torch.bfloat16), K0.shape[2],
+                             _ptr(m, torch.int32), _stream(stream)), "dynts_prefill")
+
+
+def dynts_append(ctx, layer, k_new, v_new, s_new=None, active=None, stream=None):
+    _check(lib.dynts_append(ctx, layer, _ptr(k_new, torch.bfloat16), _ptr(v_new, torch.bfloat16),
+                            _ptr(s_new, torch.float32), _ptr(active, torch.uint8), _stream(stream)), "dynts_append")
+
+
+def dynts_decode_attend(ctx, layer, q, out, lse=None, active=None, stream=None):
+    _check(lib.dynts_decode_attend(ctx, layer, _ptr(q, torch.bfloat16), _ptr(active, torch.uint8),
+                                   _ptr(out, torch.float32), _ptr(lse, torch.float32), _stream(stream)),
+           "dynts_decode_attend")
+
+
+def dynts_update_scores(ctx, layer, stream=None):
+    _check(lib.dynts_update_scores(ctx, layer, _stream(stream)), "dynts_update_scores")
+
+
+def dynts_decode_attend_update(ctx, layer, q, out, lse=None, active=None, stream=None):
+    _check(lib.dynts_decode_attend_update(ctx, layer, _ptr(q, torch.bfloat16), _ptr(active, torch.uint8),
+                                          _ptr(out, torch.float32), _ptr(lse, torch.float32), _stream(stream)),
+           "dynts_decode_attend_update")
+
+
+def dynts_decode_step(ctx, layer, q, k_new, v_new, out, s_new=None, active=None, lse=None, stream=None):
+    _check(lib.dynts_decode_step(ctx, layer, _ptr(q, torch.bfloat16), _ptr(k_new, torch.bfloat16),
+                                 _ptr(v_new, torch.bfloat16), _ptr(s_new, torch.float32),
+                                 _ptr(active, torch.uint8), _ptr(out, torch.float32), _ptr(lse, torch.float32),
+                                 _stream(stream)), "dynts_decode_step")
+
+
+def dynts_select_evict(ctx, layer, keep_idx, new_len, k_keep=-1, trigger=None, stream=None):
+    _check(lib.dynts_select_evict(ctx, layer, _ptr(trigger, torch.uint8), k_keep, _ptr(keep_idx, torch.int32),
+                                  keep_idx.shape[-1], _ptr(new_len, torch.int32), _stream(stream)),
+           "dynts_select_evict")
+
+
+def dynts_compact(ctx, layer, keep_idx, new_len, trigger=None, stream=None):
+    _check(lib.dynts_compact(ctx, layer, _ptr(trigger, torch.uint8), _ptr(keep_idx, torch.int32),
+                             keep_idx.shape[-1], _ptr(new_len, torch.int32), _stream(stream)), "dynts_compact")
+
+
+def dynts_decode_loop(ctx, n_steps, q, k_new, v_new, out, keep_idx=None, new_len=None, s_new=None, active=None,
+                      evict_steps=None, trigger=None, out_step_stride=0, stream=None):
+    """evict_steps: host uint8 tensor [n_steps] (CPU) or None."""
+    if evict_steps is not None:
+        assert evict_steps.device.type == "cpu" and evict_steps.dtype == torch.uint8
+    _check(lib.dynts_decode_loop(ctx, n_steps, _ptr(q, torch.bfloat16), _ptr(k_new, torch.bfloat16),
+                                 _ptr(v_new, torch.bfloat16), _ptr(s_new, torch.float32),
+                                 _ptr(active, torch.uint8), _ptr(evict_steps), _ptr(trigger, torch.uint8),
+                                 _ptr(out, torch.float32), out_step_stride, _ptr(keep_idx, torch.int32),
+                                 _ptr(new_len, torch.int32), _stream(stream)), "dynts_decode_loop")
+
+
+class Cache:
+    """Device buffers of one context, allocated with torch and bound; marshalling only."""
+
+    def __init__(self, n_layers, batch, n_q_heads, n_kv_heads, head_dim, capacity, budget, window,
+                 evict_every, softmax_scale=0.0, external_scores=False, device="cuda:0"):
+        self.cfg = make_config(n_layers, batch, n_q_heads, n_kv_heads, head_dim, capacity, budget, window,
+                               evict_every, softmax_scale,
+                               DYNTS_SCORE_EXTERNAL if external_scores else DYNTS_SCORE_ACCUMULATE)
+        self.ctx = dynts_create(self.cfg)
+        dev = torch.device(device)
+        L, Nb, Hkv, cap, d = n_layers, batch, n_kv_heads, capacity, head_dim
+        self.K = torch.zeros((L, Nb, Hkv, cap, d), dtype=torch.bfloat16, device=dev)
+        self.V = torch.zeros((L, Nb, Hkv, cap, d), dtype=torch.bfloat16, device=dev)
+        self.S = torch.zeros((L, Nb, Hkv, cap), dtype=torch.float32, device=dev)
+        self.pos = torch.zeros((L, Nb, Hkv, cap), dtype=torch.int32, device=dev)
+        self.seq_len = torch.zeros((L, Nb), dtype=torch.int32, device=dev)
+        self.next_pos = torch.zeros((L, Nb), dtype=torch.int32, device=dev)
+        self.n_prompt = torch.zeros((Nb,), dtype=torch.int32, device=dev)
+        self.status = torch.zeros((1,), dtype=torch.int32, device=dev)
+        self.workspace = torch.zeros((dynts_workspace_bytes(self.cfg),), dtype=torch.uint8, device=dev)
+        self.keep_idx = torch.zeros((Nb, Hkv, cap), dtype=torch.int32, device=dev)
+        self.new_len = torch.zeros((Nb,), dtype=torch.int32, device=dev)
+        dynts_bind(self.ctx, self.K, self.V, self.S, self.pos, self.seq_len, self.next_pos, self.n_prompt,
+                   self.workspace, self.status)
+
+    @classmethod
+    def for_workload(cls, wl, device="cuda:0", n_layers=None):
+        return cls(wl.n_layers if n_layers is None else n_layers, wl.batch, wl.n_q_heads, wl.n_kv_heads,
+                   wl.head_dim, wl.capacity, wl.budget, wl.window, wl.evict_every,
+                   external_scores=wl.external_scores, device=device)
+
+    def close(self):
+        if self.ctx is not None:
+            dynts_destroy(self.ctx)
+            self.ctx = None
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass

@@ -1,0 +1,180 @@
+// Eviction (Sec. 4.2): stable in-place gather of the retained rows, plus the small
+// bookkeeping kernels (prompt fill, append) that write cache rows.
+//
+// In-place safety: keep_idx is strictly ascending, so source >= destination for every row.
+// A workgroup walks its unit in ascending tiles of kCompactRows destinations; it loads the
+// whole tile's source rows into registers, meets at a barrier, then stores.  The sources of
+// any later tile lie at or beyond the end of this tile's destinations, so no row is
+// overwritten before it has been read.  Rows before the first evicted slot do not move and
+// are skipped.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace dynts {
+
+constexpr int kCompactThreads = 256;
+constexpr int kCompactUnroll = 4;
+
+struct CompactParams {
+  uint16_t *K, *V;          // [Nb][Hkv][cap][D]
+  float *S;                 // [Nb][Hkv][cap]
+  int32_t *pos;             // [Nb][Hkv][cap]
+  int32_t *seq_len;         // [Nb]
+  const uint8_t *trigger;   // [Nb] or null
+  const int32_t *keep_idx;  // [Nb][Hkv][keep_stride]
+  const int32_t *new_len;   // [Nb]
+  int Hkv, cap, keep_stride;
+};
+
+__device__ __forceinline__ int clamp_slot(int v, int cap) { return v < 0 ? 0 : (v >= cap ? cap - 1 : v); }
+
+// grid (3, Hkv, Nb): x = 0 moves K rows, 1 moves V rows, 2 moves S and pos.
+template <int D>
+__global__ __launch_bounds__(kCompactThreads) void compact_kernel(const CompactParams p) {
+  constexpr int LPR = D / 8;                        // lanes per row (16 bytes each)
+  constexpr int ROWS = kCompactThreads / LPR;       // rows per pass
+  constexpr int TILE = ROWS * kCompactUnroll;       // destinations per barrier
+  __shared__ int sh_first;
+  const int tid = threadIdx.x;
+  const int what = blockIdx.x, h = blockIdx.y, b = blockIdx.z;
+  if (p.trigger && !p.trigger[b]) return;
+  int m = p.new_len[b];
+  m = m < 0 ? 0 : (m > p.cap ? p.cap : m);
+  if (m > p.keep_stride) m = p.keep_stride;
+  const size_t unit = (size_t)b * p.Hkv + h;
+  const int32_t *ku = p.keep_idx + unit * (size_t)p.keep_stride;
+
+  // first destination whose source differs (keep_idx[i] == i is true on a prefix only)
+  if (tid == 0) {
+    int lo = 0, hi = m;
+    while (lo < hi) {
+      int mid = (lo + hi) >> 1;
+      if (ku[mid] == mid) lo = mid + 1; else hi = mid;
+    }
+    sh_first = lo;
+  }
+  __syncthreads();
+  const int first = sh_first;
+
+  if (what < 2) {
+    uint16_t *base = (what == 0 ? p.K : p.V) + unit * (size_t)p.cap * D;
+    const int r = tid / LPR, piece = tid % LPR;
+    for (int i0 = first; i0 < m; i0 += TILE) {
+      uint4 buf[kCompactUnroll];
+#pragma unroll
+      for (int u = 0; u < kCompactUnroll; ++u) {
+        int i = i0 + u * ROWS + r;
+        if (i < m) {
+          int src = clamp_slot(ku[i], p.cap);
+          buf[u] = *reinterpret_cast<const uint4 *>(base + (size_t)src * D + 8 * piece);
+        }
+      }
+      __syncthreads();
+#pragma unroll
+      for (int u = 0; u < kCompactUnroll; ++u) {
+        int i = i0 + u * ROWS + r;
+        if (i < m) *reinterpret_cast<uint4 *>(base + (size_t)i * D + 8 * piece) = buf[u];
+      }
+    }
+  } else {
+    float *Su = p.S + unit * (size_t)p.cap;
+    int32_t *pu = p.pos + unit * (size_t)p.cap;
+    for (int i0 = first; i0 < m; i0 += kCompactThreads) {
+      int i = i0 + tid;
+      float s = 0.f;
+      int32_t q = 0;
+      if (i < m) {
+        int src = clamp_slot(ku[i], p.cap);
+        s = Su[src];
+        q = pu[src];
+      }
+      __syncthreads();
+      if (i < m) {
+        Su[i] = s;
+        pu[i] = q;
+      }
+    }
+    if (h == 0 && tid == 0) p.seq_len[b] = m;
+  }
+}
+
+struct PrefillParams {
+  uint16_t *K, *V;
+  float *S;
+  int32_t *pos, *seq_len, *next_pos, *n_prompt;
+  const uint16_t *K0, *V0;  // [Nb][Hkv][m_max][D]
+  const int32_t *m;         // [Nb]
+  int Hkv, cap, m_max;
+};
+
+// grid (ceil(m_max / rows-per-block), Hkv, Nb)
+template <int D>
+__global__ __launch_bounds__(256) void prefill_kernel(const PrefillParams p) {
+  constexpr int LPR = D / 8, ROWS = 256 / LPR;
+  const int tid = threadIdx.x, h = blockIdx.y, b = blockIdx.z;
+  int mb = p.m[b];
+  mb = mb < 0 ? 0 : (mb > p.m_max ? p.m_max : mb);
+  mb = mb > p.cap ? p.cap : mb;
+  const size_t unit = (size_t)b * p.Hkv + h;
+  const int row = blockIdx.x * ROWS + tid / LPR, piece = tid % LPR;
+  if (row < mb) {
+    const size_t src = (unit * p.m_max + row) * D + 8 * piece;
+    const size_t dst = (unit * (size_t)p.cap + row) * D + 8 * piece;
+    *reinterpret_cast<uint4 *>(p.K + dst) = *reinterpret_cast<const uint4 *>(p.K0 + src);
+    *reinterpret_cast<uint4 *>(p.V + dst) = *reinterpret_cast<const uint4 *>(p.V0 + src);
+    if (piece == 0) {
+      p.S[unit * (size_t)p.cap + row] = INFINITY;
+      p.pos[unit * (size_t)p.cap + row] = row;
+    }
+  }
+  if (blockIdx.x == 0 && h == 0 && tid == 0) {
+    p.seq_len[b] = mb;
+    p.next_pos[b] = mb;
+    p.n_prompt[b] = mb;
+  }
+}
+
+struct AppendParams {
+  uint16_t *K, *V;
+  float *S;
+  int32_t *pos, *seq_len, *next_pos;
+  const uint16_t *k_new, *v_new;  // [Nb][Hkv][D]
+  const float *s_new;             // [Nb][Hkv] or null
+  const uint8_t *active;
+  int32_t *status;
+  int Hkv, cap;
+};
+
+// grid (Nb), block Hkv * D/8 threads rounded up to 64: every thread copies 16 bytes of K and of V.
+// seq_len/next_pos are advanced by thread 0 after a barrier so that all heads read the old length.
+template <int D>
+__global__ void append_kernel(const AppendParams p) {
+  constexpr int LPR = D / 8;
+  const int b = blockIdx.x, tid = threadIdx.x;
+  if (p.active && !p.active[b]) return;
+  const int n = p.seq_len[b];
+  const int np = p.next_pos[b];
+  if (n < 0 || n >= p.cap) {
+    if (tid == 0) atomicOr(p.status, 1);
+    return;
+  }
+  const int h = tid / LPR, piece = tid % LPR;
+  if (h < p.Hkv) {
+    const size_t unit = (size_t)b * p.Hkv + h;
+    const size_t dst = (unit * (size_t)p.cap + n) * D + 8 * piece;
+    *reinterpret_cast<uint4 *>(p.K + dst) = *reinterpret_cast<const uint4 *>(p.k_new + unit * D + 8 * piece);
+    *reinterpret_cast<uint4 *>(p.V + dst) = *reinterpret_cast<const uint4 *>(p.v_new + unit * D + 8 * piece);
+    if (piece == 0) {
+      p.S[unit * (size_t)p.cap + n] = p.s_new ? p.s_new[unit] : 0.f;
+      p.pos[unit * (size_t)p.cap + n] = np;
+    }
+  }
+  __syncthreads();
+  if (tid == 0) {
+    p.seq_len[b] = n + 1;
+    p.next_pos[b] = np + 1;
+  }
+}
+
+}  // namespace dynts

@@ -1,0 +1,402 @@
+// Host side of the C ABI declared in include/dynts.h: argument checks, workspace layout and
+// kernel launches.  Nothing here allocates device memory or synchronises the host.
+#include "../../include/dynts.h"
+
+#include <hip/hip_runtime.h>
+
+#include <cmath>
+#include <cstring>
+#include <new>
+#include <vector>
+
+#include "attend.hpp"
+#include "compact.hpp"
+#include "select.hpp"
+
+namespace {
+
+constexpr size_t kAlign = 256;
+constexpr int kSelectLdsMax = 16384;  // candidates whose keys are cached in LDS (64 KiB)
+
+size_t align_up(size_t v) { return (v + kAlign - 1) / kAlign * kAlign; }
+
+struct Plan {
+  int G = 0, chunk = 0, nsplit = 0;
+  size_t off_part_o = 0, off_part_ml = 0, off_ncur = 0, off_qprev = 0, off_mlprev = 0, off_nprev = 0;
+  size_t bytes = 0;
+};
+
+int check_config(const dynts_config *c) {
+  if (!c) return DYNTS_ENULL;
+  if (c->n_layers <= 0 || c->batch <= 0 || c->n_q_heads <= 0 || c->n_kv_heads <= 0) return DYNTS_EINVAL;
+  if (c->budget < 0 || c->window < 0 || c->evict_every <= 0 || c->capacity <= 0) return DYNTS_EINVAL;
+  if (c->score_mode != DYNTS_SCORE_ACCUMULATE && c->score_mode != DYNTS_SCORE_EXTERNAL) return DYNTS_EINVAL;
+  if (!(c->softmax_scale >= 0.f) || std::isinf(c->softmax_scale)) return DYNTS_EINVAL;
+  if (c->head_dim != 64 && c->head_dim != 128) return DYNTS_ESHAPE;
+  if (c->n_q_heads % c->n_kv_heads) return DYNTS_ESHAPE;
+  if (c->n_q_heads / c->n_kv_heads > 16) return DYNTS_ESHAPE;
+  if (c->n_kv_heads * (c->head_dim / 8) > 1024) return DYNTS_ESHAPE;
+  if (c->batch > 65535 || c->n_kv_heads > 65535) return DYNTS_ESHAPE;
+  if ((long long)c->capacity < (long long)c->budget + c->window + c->evict_every) return DYNTS_ECAPACITY;
+  return DYNTS_OK;
+}
+
+// Split every (sequence, KV head) cache into chunks of whole 128-slot quanta so that the
+// grid has a few workgroups per compute unit without drowning in partials.
+Plan make_plan(const dynts_config &c) {
+  Plan p;
+  p.G = c.n_q_heads / c.n_kv_heads;
+  const long long units = (long long)c.batch * c.n_kv_heads;
+  const int quanta = (c.capacity + dynts::kChunkQuantum - 1) / dynts::kChunkQuantum;
+  const long long target = 256LL * 8;  // workgroups wanted in flight
+  int per = 1;                         // quanta per chunk
+  while (per < quanta && units * ((quanta + per) / (per + 1)) >= target) ++per;
+  p.chunk = per * dynts::kChunkQuantum;
+  p.nsplit = (c.capacity + p.chunk - 1) / p.chunk;
+  const size_t rows = (size_t)units * p.nsplit * p.G;
+  size_t off = 0;
+  p.off_part_o = off;  off = align_up(off + rows * c.head_dim * sizeof(float));
+  p.off_part_ml = off; off = align_up(off + rows * 2 * sizeof(float));
+  p.off_ncur = off;    off = align_up(off + (size_t)c.batch * sizeof(int32_t));
+  const size_t LB = (size_t)c.n_layers * c.batch;
+  p.off_qprev = off;   off = align_up(off + LB * c.n_q_heads * c.head_dim * sizeof(uint16_t));
+  p.off_mlprev = off;  off = align_up(off + LB * c.n_q_heads * 2 * sizeof(float));
+  p.off_nprev = off;   off = align_up(off + LB * sizeof(int32_t));
+  p.bytes = off;
+  return p;
+}
+
+}  // namespace
+
+struct dynts_ctx {
+  dynts_config cfg;
+  Plan plan;
+  float scale_log2;
+  bool bound = false;
+  uint16_t *K = nullptr, *V = nullptr;
+  float *S = nullptr;
+  int32_t *pos = nullptr, *seq_len = nullptr, *next_pos = nullptr, *n_prompt = nullptr, *status = nullptr;
+  unsigned char *ws = nullptr;
+  std::vector<unsigned char> pending;  // per layer: a score update is owed
+};
+
+namespace {
+
+int launch_status() { return hipGetLastError() == hipSuccess ? DYNTS_OK : DYNTS_EHIP; }
+
+int check_call(const dynts_ctx *ctx, int32_t layer) {
+  if (!ctx) return DYNTS_ENULL;
+  if (!ctx->bound) return DYNTS_ENOTBOUND;
+  if (layer < 0 || layer >= ctx->cfg.n_layers) return DYNTS_EINVAL;
+  return DYNTS_OK;
+}
+
+struct LayerView {
+  uint16_t *K, *V;
+  float *S;
+  int32_t *pos, *seq_len, *next_pos;
+  uint16_t *qprev;
+  float *mlprev;
+  int32_t *nprev;
+};
+
+LayerView layer_view(const dynts_ctx *ctx, int layer) {
+  const dynts_config &c = ctx->cfg;
+  const size_t units = (size_t)c.batch * c.n_kv_heads;
+  const size_t rows = units * c.capacity;
+  LayerView v;
+  v.K = ctx->K + (size_t)layer * rows * c.head_dim;
+  v.V = ctx->V + (size_t)layer * rows * c.head_dim;
+  v.S = ctx->S + (size_t)layer * rows;
+  v.pos = ctx->pos + (size_t)layer * rows;
+  v.seq_len = ctx->seq_len + (size_t)layer * c.batch;
+  v.next_pos = ctx->next_pos + (size_t)layer * c.batch;
+  const size_t LBq = (size_t)layer * c.batch * c.n_q_heads;
+  v.qprev = reinterpret_cast<uint16_t *>(ctx->ws + ctx->plan.off_qprev) + LBq * c.head_dim;
+  v.mlprev = reinterpret_cast<float *>(ctx->ws + ctx->plan.off_mlprev) + LBq * 2;
+  v.nprev = reinterpret_cast<int32_t *>(ctx->ws + ctx->plan.off_nprev) + (size_t)layer * c.batch;
+  return v;
+}
+
+template <int D, bool ATTEND, bool PENDING, bool APPEND>
+void launch_partial(const dynts::AttendParams &p, dim3 grid, hipStream_t st) {
+  hipLaunchKernelGGL((dynts::attend_partial_kernel<D, ATTEND, PENDING, APPEND>), grid, dim3(dynts::kThreads), 0, st, p);
+}
+
+template <int D>
+void launch_partial_d(const dynts::AttendParams &p, dim3 grid, hipStream_t st, bool attend, bool pending,
+                      bool append) {
+  if (!attend) return launch_partial<D, false, true, false>(p, grid, st);
+  if (pending) {
+    if (append) return launch_partial<D, true, true, true>(p, grid, st);
+    return launch_partial<D, true, true, false>(p, grid, st);
+  }
+  if (append) return launch_partial<D, true, false, true>(p, grid, st);
+  return launch_partial<D, true, false, false>(p, grid, st);
+}
+
+// attend (optionally with fused append) and/or the deferred score update of one layer
+int run_attend(dynts_ctx *ctx, int layer, const uint16_t *q, const uint16_t *k_new, const uint16_t *v_new,
+               const float *s_new, const uint8_t *active, float *out, float *lse, bool attend,
+               bool apply_pending, bool append, hipStream_t st) {
+  const dynts_config &c = ctx->cfg;
+  const Plan &pl = ctx->plan;
+  const LayerView lv = layer_view(ctx, layer);
+  const bool track = c.score_mode == DYNTS_SCORE_ACCUMULATE;
+
+  dynts::AttendParams p;
+  p.K = lv.K; p.V = lv.V; p.S = lv.S; p.pos = lv.pos;
+  p.seq_len = lv.seq_len; p.n_prompt = ctx->n_prompt; p.next_pos = lv.next_pos;
+  p.q = q; p.k_new = k_new; p.v_new = v_new; p.s_new = s_new; p.active = active;
+  p.qprev = lv.qprev; p.mlprev = lv.mlprev; p.nprev = lv.nprev;
+  p.part_o = reinterpret_cast<float *>(ctx->ws + pl.off_part_o);
+  p.part_ml = reinterpret_cast<float *>(ctx->ws + pl.off_part_ml);
+  p.ncur = reinterpret_cast<int32_t *>(ctx->ws + pl.off_ncur);
+  p.status = ctx->status;
+  p.Nb = c.batch; p.Hq = c.n_q_heads; p.Hkv = c.n_kv_heads; p.G = pl.G; p.cap = c.capacity;
+  p.chunk = pl.chunk; p.nsplit = pl.nsplit; p.scale_log2 = ctx->scale_log2;
+
+  const dim3 grid(pl.nsplit, c.n_kv_heads, c.batch);
+  if (c.head_dim == 128) launch_partial_d<128>(p, grid, st, attend, apply_pending, append);
+  else launch_partial_d<64>(p, grid, st, attend, apply_pending, append);
+  int rc = launch_status();
+  if (rc != DYNTS_OK) return rc;
+  if (!attend) return DYNTS_OK;
+
+  dynts::MergeParams m;
+  m.part_o = p.part_o; m.part_ml = p.part_ml; m.ncur = p.ncur; m.q = q; m.out = out; m.lse = lse;
+  m.qprev = track ? lv.qprev : nullptr; m.mlprev = lv.mlprev; m.nprev = lv.nprev;
+  m.seq_len = lv.seq_len; m.next_pos = lv.next_pos;
+  m.Hq = c.n_q_heads; m.Hkv = c.n_kv_heads; m.G = pl.G; m.chunk = pl.chunk; m.nsplit = pl.nsplit;
+  m.appended = append ? 1 : 0;
+  const dim3 mgrid(c.n_q_heads, c.batch);
+  if (c.head_dim == 128) hipLaunchKernelGGL((dynts::attend_merge_kernel<128>), mgrid, dim3(128), 0, st, m);
+  else hipLaunchKernelGGL((dynts::attend_merge_kernel<64>), mgrid, dim3(64), 0, st, m);
+  return launch_status();
+}
+
+}  // namespace
+
+extern "C" {
+
+int dynts_version(void) { return 100; }
+
+const char *dynts_strerror(int code) {
+  switch (code) {
+    case DYNTS_OK: return "ok";
+    case DYNTS_EINVAL: return "argument out of range";
+    case DYNTS_ENULL: return "required pointer is null";
+    case DYNTS_ESHAPE: return "unsupported shape (head_dim must be 64 or 128, group size <= 16, n_q_heads % n_kv_heads == 0)";
+    case DYNTS_ECAPACITY: return "capacity or index stride too small";
+    case DYNTS_ENOTBOUND: return "no buffers bound (call dynts_bind)";
+    case DYNTS_EWORKSPACE: return "workspace too small or misaligned";
+    case DYNTS_EHIP: return "HIP runtime error at kernel launch";
+    case DYNTS_EPENDING: return "a score update is outstanding (call dynts_update_scores first)";
+    default: return "unknown error";
+  }
+}
+
+int dynts_create(const dynts_config *cfg, dynts_ctx **out) {
+  if (!out) return DYNTS_ENULL;
+  *out = nullptr;
+  int rc = check_config(cfg);
+  if (rc != DYNTS_OK) return rc;
+  dynts_ctx *ctx = new (std::nothrow) dynts_ctx();
+  if (!ctx) return DYNTS_EINVAL;
+  ctx->cfg = *cfg;
+  ctx->plan = make_plan(*cfg);
+  const float scale = cfg->softmax_scale > 0.f ? cfg->softmax_scale : 1.0f / std::sqrt((float)cfg->head_dim);
+  ctx->scale_log2 = scale * 1.4426950408889634f;
+  ctx->pending.assign((size_t)cfg->n_layers, 0);
+  *out = ctx;
+  return DYNTS_OK;
+}
+
+int dynts_destroy(dynts_ctx *ctx) {
+  if (!ctx) return DYNTS_ENULL;
+  delete ctx;
+  return DYNTS_OK;
+}
+
+size_t dynts_workspace_bytes(const dynts_config *cfg) {
+  if (check_config(cfg) != DYNTS_OK) return 0;
+  return make_plan(*cfg).bytes;
+}
+
+int dynts_bind(dynts_ctx *ctx, uint16_t *K, uint16_t *V, float *S, int32_t *pos, int32_t *seq_len,
+               int32_t *next_pos, int32_t *n_prompt, void *workspace, size_t workspace_bytes, int32_t *status) {
+  if (!ctx || !K || !V || !S || !pos || !seq_len || !next_pos || !n_prompt || !workspace || !status) return DYNTS_ENULL;
+  if (workspace_bytes < ctx->plan.bytes || (reinterpret_cast<uintptr_t>(workspace) % kAlign)) return DYNTS_EWORKSPACE;
+  if ((reinterpret_cast<uintptr_t>(K) | reinterpret_cast<uintptr_t>(V)) % 16) return DYNTS_EINVAL;
+  ctx->K = K; ctx->V = V; ctx->S = S; ctx->pos = pos; ctx->seq_len = seq_len; ctx->next_pos = next_pos;
+  ctx->n_prompt = n_prompt; ctx->ws = static_cast<unsigned char *>(workspace); ctx->status = status;
+  ctx->pending.assign(ctx->pending.size(), 0);
+  ctx->bound = true;
+  return DYNTS_OK;
+}
+
+int dynts_prefill(dynts_ctx *ctx, int32_t layer, const uint16_t *K0, const uint16_t *V0, int32_t m_max,
+                  const int32_t *m, void *stream) {
+  int rc = check_call(ctx, layer);
+  if (rc != DYNTS_OK) return rc;
+  if (!K0 || !V0 || !m) return DYNTS_ENULL;
+  if (m_max <= 0) return DYNTS_EINVAL;
+  if (m_max > ctx->cfg.capacity) return DYNTS_ECAPACITY;
+  if ((reinterpret_cast<uintptr_t>(K0) | reinterpret_cast<uintptr_t>(V0)) % 16) return DYNTS_EINVAL;
+  const dynts_config &c = ctx->cfg;
+  const LayerView lv = layer_view(ctx, layer);
+  dynts::PrefillParams p{lv.K, lv.V, lv.S, lv.pos, lv.seq_len, lv.next_pos, ctx->n_prompt, K0, V0, m,
+                         c.n_kv_heads, c.capacity, m_max};
+  const int rows = 256 / (c.head_dim / 8);
+  const dim3 grid((m_max + rows - 1) / rows, c.n_kv_heads, c.batch);
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  if (c.head_dim == 128) hipLaunchKernelGGL((dynts::prefill_kernel<128>), grid, dim3(256), 0, st, p);
+  else hipLaunchKernelGGL((dynts::prefill_kernel<64>), grid, dim3(256), 0, st, p);
+  ctx->pending[layer] = 0;
+  return launch_status();
+}
+
+int dynts_append(dynts_ctx *ctx, int32_t layer, const uint16_t *k_new, const uint16_t *v_new, const float *s_new,
+                 const uint8_t *active, void *stream) {
+  int rc = check_call(ctx, layer);
+  if (rc != DYNTS_OK) return rc;
+  if (!k_new || !v_new) return DYNTS_ENULL;
+  const dynts_config &c = ctx->cfg;
+  if (c.score_mode == DYNTS_SCORE_EXTERNAL && !s_new) return DYNTS_ENULL;
+  if ((reinterpret_cast<uintptr_t>(k_new) | reinterpret_cast<uintptr_t>(v_new)) % 16) return DYNTS_EINVAL;
+  const LayerView lv = layer_view(ctx, layer);
+  dynts::AppendParams p{lv.K, lv.V, lv.S, lv.pos, lv.seq_len, lv.next_pos, k_new, v_new,
+                        c.score_mode == DYNTS_SCORE_EXTERNAL ? s_new : nullptr, active, ctx->status,
+                        c.n_kv_heads, c.capacity};
+  const int threads = (c.n_kv_heads * (c.head_dim / 8) + 63) / 64 * 64;
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  if (c.head_dim == 128) hipLaunchKernelGGL((dynts::append_kernel<128>), dim3(c.batch), dim3(threads), 0, st, p);
+  else hipLaunchKernelGGL((dynts::append_kernel<64>), dim3(c.batch), dim3(threads), 0, st, p);
+  return launch_status();
+}
+
+int dynts_decode_attend(dynts_ctx *ctx, int32_t layer, const uint16_t *q, const uint8_t *active, float *out,
+                        float *lse, void *stream) {
+  int rc = check_call(ctx, layer);
+  if (rc != DYNTS_OK) return rc;
+  if (!q || !out) return DYNTS_ENULL;
+  if (reinterpret_cast<uintptr_t>(q) % 16) return DYNTS_EINVAL;
+  rc = run_attend(ctx, layer, q, nullptr, nullptr, nullptr, active, out, lse, true, false, false,
+                  static_cast<hipStream_t>(stream));
+  if (rc == DYNTS_OK) ctx->pending[layer] = ctx->cfg.score_mode == DYNTS_SCORE_ACCUMULATE;
+  return rc;
+}
+
+int dynts_update_scores(dynts_ctx *ctx, int32_t layer, void *stream) {
+  int rc = check_call(ctx, layer);
+  if (rc != DYNTS_OK) return rc;
+  if (!ctx->pending[layer]) return DYNTS_OK;
+  rc = run_attend(ctx, layer, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, false, true, false,
+                  static_cast<hipStream_t>(stream));
+  if (rc == DYNTS_OK) ctx->pending[layer] = 0;
+  return rc;
+}
+
+int dynts_decode_attend_update(dynts_ctx *ctx, int32_t layer, const uint16_t *q, const uint8_t *active,
+                               float *out, float *lse, void *stream) {
+  int rc = check_call(ctx, layer);
+  if (rc != DYNTS_OK) return rc;
+  if (!q || !out) return DYNTS_ENULL;
+  if (reinterpret_cast<uintptr_t>(q) % 16) return DYNTS_EINVAL;
+  rc = run_attend(ctx, layer, q, nullptr, nullptr, nullptr, active, out, lse, true, ctx->pending[layer] != 0,
+                  false, static_cast<hipStream_t>(stream));
+  if (rc == DYNTS_OK) ctx->pending[layer] = ctx->cfg.score_mode == DYNTS_SCORE_ACCUMULATE;
+  return rc;
+}
+
+int dynts_decode_step(dynts_ctx *ctx, int32_t layer, const uint16_t *q, const uint16_t *k_new,
+                      const uint16_t *v_new, const float *s_new, const uint8_t *active, float *out, float *lse,
+                      void *stream) {
+  int rc = check_call(ctx, layer);
+  if (rc != DYNTS_OK) return rc;
+  if (!q || !out || !k_new || !v_new) return DYNTS_ENULL;
+  const bool ext = ctx->cfg.score_mode == DYNTS_SCORE_EXTERNAL;
+  if (ext && !s_new) return DYNTS_ENULL;
+  if ((reinterpret_cast<uintptr_t>(q) | reinterpret_cast<uintptr_t>(k_new) | reinterpret_cast<uintptr_t>(v_new)) % 16)
+    return DYNTS_EINVAL;
+  rc = run_attend(ctx, layer, q, k_new, v_new, ext ? s_new : nullptr, active, out, lse, true,
+                  ctx->pending[layer] != 0, true, static_cast<hipStream_t>(stream));
+  if (rc == DYNTS_OK) ctx->pending[layer] = !ext;
+  return rc;
+}
+
+int dynts_select_evict(dynts_ctx *ctx, int32_t layer, const uint8_t *trigger, int32_t k_keep, int32_t *keep_idx,
+                       int32_t keep_stride, int32_t *new_len, void *stream) {
+  int rc = check_call(ctx, layer);
+  if (rc != DYNTS_OK) return rc;
+  if (!keep_idx || !new_len) return DYNTS_ENULL;
+  if (keep_stride <= 0) return DYNTS_ECAPACITY;
+  const dynts_config &c = ctx->cfg;
+  if (k_keep < 0) k_keep = c.budget;
+  rc = dynts_update_scores(ctx, layer, stream);
+  if (rc != DYNTS_OK) return rc;
+  const LayerView lv = layer_view(ctx, layer);
+  dynts::SelectParams p{lv.S, lv.seq_len, ctx->n_prompt, trigger, keep_idx, new_len, ctx->status,
+                        c.n_kv_heads, c.capacity, c.window, k_keep, keep_stride};
+  const dim3 grid(c.n_kv_heads, c.batch);
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  if (c.capacity <= kSelectLdsMax)
+    hipLaunchKernelGGL((dynts::select_kernel<true>), grid, dim3(dynts::kSelThreads), (size_t)c.capacity * 4, st, p);
+  else
+    hipLaunchKernelGGL((dynts::select_kernel<false>), grid, dim3(dynts::kSelThreads), 0, st, p);
+  return launch_status();
+}
+
+int dynts_compact(dynts_ctx *ctx, int32_t layer, const uint8_t *trigger, const int32_t *keep_idx,
+                  int32_t keep_stride, const int32_t *new_len, void *stream) {
+  int rc = check_call(ctx, layer);
+  if (rc != DYNTS_OK) return rc;
+  if (!keep_idx || !new_len) return DYNTS_ENULL;
+  if (keep_stride <= 0) return DYNTS_ECAPACITY;
+  if (ctx->pending[layer]) return DYNTS_EPENDING;
+  const dynts_config &c = ctx->cfg;
+  const LayerView lv = layer_view(ctx, layer);
+  dynts::CompactParams p{lv.K, lv.V, lv.S, lv.pos, lv.seq_len, trigger, keep_idx, new_len,
+                         c.n_kv_heads, c.capacity, keep_stride};
+  const dim3 grid(3, c.n_kv_heads, c.batch);
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  if (c.head_dim == 128) hipLaunchKernelGGL((dynts::compact_kernel<128>), grid, dim3(dynts::kCompactThreads), 0, st, p);
+  else hipLaunchKernelGGL((dynts::compact_kernel<64>), grid, dim3(dynts::kCompactThreads), 0, st, p);
+  return launch_status();
+}
+
+int dynts_decode_loop(dynts_ctx *ctx, int32_t n_steps, const uint16_t *q, const uint16_t *k_new,
+                      const uint16_t *v_new, const float *s_new, const uint8_t *active, const uint8_t *evict_steps,
+                      const uint8_t *trigger, float *out, size_t out_step_stride, int32_t *keep_idx,
+                      int32_t *new_len, void *stream) {
+  int rc = check_call(ctx, 0);
+  if (rc != DYNTS_OK) return rc;
+  if (n_steps < 0) return DYNTS_EINVAL;
+  if (!q || !k_new || !v_new || !out) return DYNTS_ENULL;
+  const dynts_config &c = ctx->cfg;
+  const bool ext = c.score_mode == DYNTS_SCORE_EXTERNAL;
+  if (ext && !s_new) return DYNTS_ENULL;
+  if (evict_steps && (!keep_idx || !new_len)) return DYNTS_ENULL;
+  const size_t q_layer = (size_t)c.batch * c.n_q_heads * c.head_dim;
+  const size_t kv_layer = (size_t)c.batch * c.n_kv_heads * c.head_dim;
+  for (int i = 0; i < n_steps; ++i) {
+    const uint8_t *act = active ? active + (size_t)i * c.batch : nullptr;
+    const float *sn = ext ? s_new + (size_t)i * c.batch * c.n_kv_heads : nullptr;
+    for (int l = 0; l < c.n_layers; ++l) {
+      const size_t sl = (size_t)i * c.n_layers + l;
+      rc = dynts_decode_step(ctx, l, q + sl * q_layer, k_new + sl * kv_layer, v_new + sl * kv_layer, sn, act,
+                             out + (size_t)i * out_step_stride + (size_t)l * q_layer, nullptr, stream);
+      if (rc != DYNTS_OK) return rc;
+      if (evict_steps && evict_steps[i]) {
+        const uint8_t *trig = trigger ? trigger + (size_t)i * c.batch : nullptr;
+        rc = dynts_select_evict(ctx, l, trig, c.budget, keep_idx, c.capacity, new_len, stream);
+        if (rc != DYNTS_OK) return rc;
+        rc = dynts_compact(ctx, l, trig, keep_idx, c.capacity, new_len, stream);
+        if (rc != DYNTS_OK) return rc;
+      }
+    }
+  }
+  return DYNTS_OK;
+}
+
+}  // extern "C"

@@ -1,0 +1,201 @@
+"""GPU parity: the HIP path, called through the C ABI, against the float64 oracle on the same
+seeded synthetic inputs."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import dynts_oracle as orc
+from paper_2601_18383_amd import configs, synth
+from tests.helpers import SideBySide, assert_close, f64, i32
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def B():
+    from paper_2601_18383_amd import binding
+    return binding
+
+
+def _bf16(rng, *shape, scale=1.0):
+    return torch.from_numpy(rng.standard_normal(shape).astype(np.float32) * scale).to(torch.bfloat16)
+
+
+def _pair(B, Nb, Hq, Hkv, d, M_max, budget, window, E, mode, external=False, scale=0.0):
+    cap = M_max + budget + window + E
+    cache = B.Cache(1, Nb, Hq, Hkv, d, cap, budget, window, E, softmax_scale=scale, external_scores=external)
+    o = orc.OracleLayer(Nb, Hq, Hkv, d, cap, budget, window, E,
+                        softmax_scale=scale if scale else None, external_scores=external)
+    return SideBySide(B, cache, 0, o, mode), cap
+
+
+@pytest.mark.parametrize("mode", ["unfused", "fused", "step"])
+@pytest.mark.parametrize("d,Hq,Hkv", [(64, 8, 2), (128, 28, 4), (128, 6, 6), (128, 16, 1)])
+def test_trajectory_small(B, mode, d, Hq, Hkv):
+    """Several tiles, a ragged tail, ragged prompts, several evictions, a sequence that finishes early."""
+    rng = np.random.default_rng(100 + d + Hq)
+    Nb, M_max, budget, window, E, T = 3, 37, 150, 19, 13, 260
+    sbs, cap = _pair(B, Nb, Hq, Hkv, d, M_max, budget, window, E, mode)
+    m = [37, 5, 20]
+    sbs.prefill(_bf16(rng, Nb, Hkv, M_max, d), _bf16(rng, Nb, Hkv, M_max, d), m)
+    last = [T, 90, T]
+    for t in range(1, T + 1):
+        active = np.array([t <= last[b] for b in range(Nb)], np.uint8)
+        q = _bf16(rng, Nb, Hq, d, scale=1.5)
+        k = _bf16(rng, Nb, Hkv, d)
+        v = _bf16(rng, Nb, Hkv, d)
+        sbs.step(q, k, v, active=active, check_scores=(t % 5 == 0 or mode == "unfused"))
+    sbs.check_scores()
+    sbs.check_state()
+    assert sbs.evictions >= 5
+    assert int(sbs.c.status.item()) == 0
+    # the finished sequence was left alone
+    assert int(sbs.c.seq_len[0, 1].item()) == sbs.o.seq_len[1]
+
+
+def test_cfg1_full_trajectory(B):
+    """Config 1 end to end: 512 steps, 22 evictions, planted critical keys."""
+    wl = configs.get("cfg1")
+    gen = synth.Synth(wl, "cpu")
+    cache = B.Cache.for_workload(wl)
+    o = orc.OracleLayer(wl.batch, wl.n_q_heads, wl.n_kv_heads, wl.head_dim, wl.capacity, wl.budget,
+                        wl.window, wl.evict_every)
+    sbs = SideBySide(B, cache, 0, o, "step")
+    K0, V0 = gen.prompt_kv(0)
+    sbs.prefill(K0, V0, [wl.prompt] * wl.batch)
+    T = wl.steps[0]
+    steps = torch.arange(1, T + 1)
+    q = gen.q(0, steps)
+    k, v = gen.kv(0, steps)
+    crit = gen.critical(0, steps)
+    for t in range(1, T + 1):
+        sbs.step(q[t - 1], k[t - 1], v[t - 1], check_scores=(t % 16 == 7))
+    sbs.check_scores()
+    sbs.check_state()
+    assert sbs.evictions == 22
+    assert o.seq_len[0] == wl.steady_len
+    # meaning check: planted critical tokens that left the local window are retained
+    left = [wl.prompt + t - 1 for t in range(1, T - wl.window + 1) if crit[t - 1, 0]]
+    kept = set(i32(cache.pos[0, 0, 0, :wl.steady_len]).tolist())
+    recall = sum(p in kept for p in left) / max(1, len(left))
+    assert recall >= 0.9, recall
+
+
+def _score_cases(rng, nc):
+    """Hand-made score arrays: long equal runs, signed zeros, denormals, infinities, negatives."""
+    cases = []
+    cases.append(np.full(nc, 0.25, np.float32))
+    cases.append(rng.integers(0, 3, nc).astype(np.float32))
+    cases.append(rng.choice(np.array([0.0, -0.0, 1e-45, -1e-45, 1e-38], np.float32), nc))
+    cases.append(rng.standard_normal(nc).astype(np.float32))
+    cases.append(np.arange(nc, dtype=np.float32))
+    cases.append(-np.arange(nc, dtype=np.float32))
+    a = rng.random(nc).astype(np.float32)
+    a[rng.integers(0, nc, 5)] = np.inf
+    a[rng.integers(0, nc, 5)] = -np.inf
+    cases.append(a)
+    a = rng.random(nc).astype(np.float32)
+    cut = np.sort(a)[nc // 2]
+    a[rng.integers(0, nc, nc // 3)] = cut  # a long run of ties exactly at a plausible cut
+    cases.append(a)
+    cases.append(np.float32(1.0) + rng.integers(0, 4, nc).astype(np.float32) * np.float32(2 ** -23))
+    return cases
+
+
+@pytest.mark.parametrize("nc,k_keep,window,M", [(300, 100, 16, 10), (2112, 2048, 128, 256), (1040, 1024, 32, 128),
+                                                  (4160, 4096, 128, 256), (70, 0, 3, 0), (33, 40, 0, 4), (1, 1, 0, 0),
+                                                  (5000, 1500, 2000, 100)])
+def test_select_bit_exact_on_given_scores(B, nc, k_keep, window, M):
+    """Selection on identical score arrays must equal the oracle's bit for bit, ties included."""
+    rng = np.random.default_rng(nc * 7 + k_keep)
+    cases = _score_cases(rng, nc + window)
+    Nb, Hkv = len(cases), 2
+    n = M + nc + window
+    cap = n + 8
+    cache = B.Cache(1, Nb, 2 * Hkv, Hkv, 64, cap, 1, window, 8, external_scores=True)
+    S = np.zeros((Nb, Hkv, cap), np.float32)
+    for b, a in enumerate(cases):
+        S[b, 0, M:n] = a
+        S[b, 1, M:n] = a[::-1]
+    S[:, :, :M] = np.inf
+    pos = np.broadcast_to(np.arange(cap, dtype=np.int32) * 3, (Nb, Hkv, cap)).copy()
+    seq_len = np.full(Nb, n, np.int32)
+    n_prompt = np.full(Nb, M, np.int32)
+    cache.S[0].copy_(torch.from_numpy(S))
+    cache.pos[0].copy_(torch.from_numpy(pos))
+    cache.seq_len[0].copy_(torch.from_numpy(seq_len))
+    cache.n_prompt.copy_(torch.from_numpy(n_prompt))
+    trig = np.ones(Nb, np.uint8)
+    trig[1] = 0
+    cache.keep_idx.fill_(-1)
+    B.dynts_select_evict(cache.ctx, 0, cache.keep_idx, cache.new_len, k_keep, torch.from_numpy(trig).cuda())
+    keep_ref, len_ref = orc.select(S.astype(np.float64), pos, seq_len, n_prompt, window, k_keep, trig)
+    assert np.array_equal(i32(cache.new_len), len_ref)
+    assert np.array_equal(i32(cache.keep_idx), keep_ref)
+    assert int(cache.status.item()) == 0
+
+
+@pytest.mark.parametrize("d", [64, 128])
+def test_compact_bit_exact(B, d):
+    rng = np.random.default_rng(5 + d)
+    Nb, Hkv, cap = 4, 3, 777
+    cache = B.Cache(1, Nb, Hkv, Hkv, d, cap, 10, 5, 5)
+    K = _bf16(rng, Nb, Hkv, cap, d)
+    V = _bf16(rng, Nb, Hkv, cap, d)
+    S = rng.random((Nb, Hkv, cap)).astype(np.float32)
+    pos = np.cumsum(rng.integers(1, 4, (Nb, Hkv, cap)), -1).astype(np.int32)
+    seq_len = np.array([777, 500, 64, 300], np.int32)
+    cache.K[0].copy_(K); cache.V[0].copy_(V)
+    cache.S[0].copy_(torch.from_numpy(S)); cache.pos[0].copy_(torch.from_numpy(pos))
+    cache.seq_len[0].copy_(torch.from_numpy(seq_len))
+    keep = np.full((Nb, Hkv, cap), -1, np.int32)
+    new_len = np.zeros(Nb, np.int32)
+    frac = [0.5, 0.97, 0.3, 1.0]
+    for b in range(Nb):
+        m = int(seq_len[b] * frac[b])
+        new_len[b] = m
+        for h in range(Hkv):
+            sel = np.sort(rng.choice(seq_len[b], m, replace=False))
+            if b == 1:  # a long unmoved prefix
+                rest = np.sort(rng.choice(np.arange(400, seq_len[b]), m - 400, replace=False))
+                sel = np.concatenate([np.arange(400), rest])
+            keep[b, h, :m] = sel
+    trig = np.array([1, 1, 0, 1], np.uint8)
+    cache.keep_idx.copy_(torch.from_numpy(keep)); cache.new_len.copy_(torch.from_numpy(new_len))
+    B.dynts_compact(cache.ctx, 0, cache.keep_idx, cache.new_len, torch.from_numpy(trig).cuda())
+    Ko, Vo, So, po, sl = f64(K), f64(V), S.astype(np.float64), pos.copy(), seq_len.copy()
+    orc.compact(Ko, Vo, So, po, sl, keep, new_len, trig)
+    assert np.array_equal(i32(cache.seq_len[0]), sl)
+    for b in range(Nb):
+        n = sl[b]
+        assert np.array_equal(f64(cache.K[0, b, :, :n]), Ko[b, :, :n])
+        assert np.array_equal(f64(cache.V[0, b, :, :n]), Vo[b, :, :n])
+        assert np.array_equal(f64(cache.S[0, b, :, :n]), So[b, :, :n])
+        assert np.array_equal(i32(cache.pos[0, b, :, :n]), po[b, :, :n])
+    # the untriggered sequence is untouched, tail included
+    assert np.array_equal(f64(cache.K[0, 2]), f64(K[2]))
+
+
+def test_attention_edge_cases(B):
+    """n = 1, one dominant key, uniform attention, large logits: closed forms on the GPU path too."""
+    rng = np.random.default_rng(9)
+    Nb, Hq, Hkv, d, cap = 4, 8, 2, 128, 600
+    cache = B.Cache(1, Nb, Hq, Hkv, d, cap, 500, 10, 10, softmax_scale=1.0)
+    o = orc.OracleLayer(Nb, Hq, Hkv, d, cap, 500, 10, 10, softmax_scale=1.0)
+    sbs = SideBySide(B, cache, 0, o, "unfused")
+    M = [1, 300, 590, 33]
+    K0 = _bf16(rng, Nb, Hkv, 590, d, scale=0.1)
+    V0 = _bf16(rng, Nb, Hkv, 590, d)
+    K0[1, :, 123] = 3.0   # a dominant key for an all-ones query: logit 384 vs ~0
+    K0[3] = 0.5           # identical keys: uniform attention
+    sbs.prefill(K0, V0, M)
+    q = torch.ones(Nb, Hq, d).to(torch.bfloat16)
+    # attend over the prompt only (no append): n = M
+    B.dynts_decode_attend(cache.ctx, 0, q.cuda(), sbs.out, sbs.lse)
+    out_ref, alpha, lse_ref = o.attend(f64(q))
+    assert_close(f64(sbs.out), out_ref, "out")
+    assert_close(f64(sbs.lse), lse_ref, "lse")
+    got = f64(sbs.out)
+    assert np.array_equal(got[0, 0], f64(V0[0, 0, 0]))                 # n = 1: the value row itself
+    assert np.allclose(got[1, 0], f64(V0[1, 0, 123]), atol=1e-6)      # one-hot
+    assert np.allclose(got[3, 5], f64(V0[3, 1, :33]).mean(0), atol=2e-3)
