@@ -1,0 +1,278 @@
+#!/usr/bin/env python3
+"""Decode-step benchmark of the DynTS hot path on one MI355X.
+
+A step is one pass of the whole path over one batch of synthetic input: for every layer the
+fused append + decode attention + deferred score update, and on trigger steps the score
+flush, top-k selection and in-place compaction -- all inside the timed region, inputs
+resident in HBM.  Prints ONE JSON line (see the README for the fields).
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload cfg3]
+"""
+import argparse
+import ctypes
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0  # MI355X published HBM3E bandwidth
+
+
+def log(*a):
+    print(*a, file=sys.stderr, flush=True)
+
+
+def algorithmic_bytes(wl, n_list, n_active):
+    """Bytes one layer-step must move (K+V rows read, scores read+written, q in, out written,
+    the appended K/V row written), for cache lengths n_list of the active sequences."""
+    d, Hkv, Hq, M = wl.head_dim, wl.n_kv_heads, wl.n_q_heads, wl.prompt
+    kv = sum(Hkv * (n * d * 2 * 2 + (n - M) * 8) for n in n_list)
+    return kv + n_active * Hq * d * (2 + 4) + 2 * n_active * Hkv * d * 2
+
+
+class HipEvents:
+    """Raw hipEvent pairs, so the library can record them around its streaming kernel."""
+
+    def __init__(self, n):
+        self.hip = ctypes.CDLL("libamdhip64.so")
+        self.hip.hipEventCreate.argtypes = [ctypes.POINTER(ctypes.c_void_p)]
+        self.hip.hipEventElapsedTime.argtypes = [ctypes.POINTER(ctypes.c_float), ctypes.c_void_p, ctypes.c_void_p]
+        self.hip.hipEventDestroy.argtypes = [ctypes.c_void_p]
+        self.pairs = []
+        for _ in range(n):
+            a, b = ctypes.c_void_p(), ctypes.c_void_p()
+            assert self.hip.hipEventCreate(ctypes.byref(a)) == 0
+            assert self.hip.hipEventCreate(ctypes.byref(b)) == 0
+            self.pairs.append((a, b))
+
+    def elapsed_ms(self, i):
+        ms = ctypes.c_float()
+        rc = self.hip.hipEventElapsedTime(ctypes.byref(ms), self.pairs[i][0], self.pairs[i][1])
+        assert rc == 0, rc
+        return ms.value
+
+    def close(self):
+        for a, b in self.pairs:
+            self.hip.hipEventDestroy(a)
+            self.hip.hipEventDestroy(b)
+
+
+def make_pools(gen, wl, t0, n, device):
+    """q [n][L][Nb][Hq][d], k/v [n][L][Nb][Hkv][d] for decode steps t0+1 .. t0+n."""
+    import torch
+    steps = torch.arange(t0 + 1, t0 + n + 1)
+    qs, ks, vs = [], [], []
+    for l in range(wl.n_layers):
+        qs.append(gen.q(l, steps))
+        k, v = gen.kv(l, steps)
+        ks.append(k)
+        vs.append(v)
+    q = torch.stack(qs, 1).contiguous()
+    k = torch.stack(ks, 1).contiguous()
+    v = torch.stack(vs, 1).contiguous()
+    s = None
+    if wl.external_scores:
+        s = gen.external_scores(steps).unsqueeze(-1).expand(n, wl.batch, wl.n_kv_heads).contiguous()
+    return q, k, v, s
+
+
+def evict_flags(wl, t0, n):
+    """Host flags of the trigger steps among t0+1 .. t0+n (every evict_every-th step once the
+    thinking tokens exceed budget + window)."""
+    import torch
+    f = torch.zeros(n, dtype=torch.uint8)
+    for i in range(n):
+        t = t0 + 1 + i
+        if t % wl.evict_every == 0 and t > wl.budget + wl.window:
+            f[i] = 1
+    return f
+
+
+def cache_len_before_step(wl, t):
+    """Slots attended at decode step t (after the append, before any eviction of that step)."""
+    E, BW = wl.evict_every, wl.budget + wl.window
+    ev = max(0, (t - 1 - BW) // E) if t - 1 > BW else 0
+    return wl.prompt + t - ev * E
+
+
+def run_gpu(args, wl):
+    import torch
+    from paper_2601_18383_amd import binding as B, synth
+
+    dev = torch.device("cuda:0")
+    props = torch.cuda.get_device_properties(0)
+    log("device: %s, %d CUs, %.0f GiB" % (props.name, props.multi_processor_count, props.total_memory / 2 ** 30))
+    gen = synth.Synth(wl, dev)
+    cache = B.Cache.for_workload(wl, device=dev)
+    L = wl.n_layers
+    for l in range(L):
+        K0, V0 = gen.prompt_kv(l)
+        m = torch.full((wl.batch,), wl.prompt, dtype=torch.int32, device=dev)
+        B.dynts_prefill(cache.ctx, l, K0, V0, m)
+    out = torch.zeros((L, wl.batch, wl.n_q_heads, wl.head_dim), dtype=torch.float32, device=dev)
+
+    # ---- bring the cache to steady state through the path itself (untimed) -----------------
+    E = wl.evict_every
+    t_steady = (wl.budget + wl.window + E) + 2 * E       # two periods past the first eviction
+    t_steady = (t_steady + E - 1) // E * E
+    lo = wl.steps[0]
+    total = t_steady + args.warmup + args.steps
+    assert total <= lo, "timed window must end before the shortest sequence finishes (%d > %d)" % (total, lo)
+    per_step = L * wl.batch * (wl.n_q_heads + 2 * wl.n_kv_heads) * wl.head_dim * 2
+    block = max(E, min(256, (1 << 30) // per_step) // E * E)   # input pool of at most 1 GiB
+    t = 0
+    t_pre = time.perf_counter()
+    while t < t_steady:
+        n = min(block, t_steady - t)
+        q, k, v, s = make_pools(gen, wl, t, n, dev)
+        B.dynts_decode_loop(cache.ctx, n, q, k, v, out, cache.keep_idx, cache.new_len, s_new=s,
+                            evict_steps=evict_flags(wl, t, n))
+        t += n
+    torch.cuda.synchronize()
+    log("steady state reached at step %d in %.1f s; seq_len[0,0]=%d status=%d" %
+        (t, time.perf_counter() - t_pre, int(cache.seq_len[0, 0]), int(cache.status[0])))
+
+    # ---- warmup + timed window, inputs resident ---------------------------------------------
+    qw, kw, vw, sw = make_pools(gen, wl, t, args.warmup, dev) if args.warmup else (None,) * 4
+    fw = evict_flags(wl, t, args.warmup)
+    qt, kt, vt, stt = make_pools(gen, wl, t + args.warmup, args.steps, dev)
+    ft = evict_flags(wl, t + args.warmup, args.steps)
+    torch.cuda.synchronize()
+    if args.warmup:
+        B.dynts_decode_loop(cache.ctx, args.warmup, qw, kw, vw, out, cache.keep_idx, cache.new_len, s_new=sw,
+                            evict_steps=fw)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    B.dynts_decode_loop(cache.ctx, args.steps, qt, kt, vt, out, cache.keep_idx, cache.new_len, s_new=stt,
+                        evict_steps=ft)
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    t_end = t + args.warmup + args.steps
+    assert int(cache.status[0]) == 0, "device status word set: %d" % int(cache.status[0])
+    assert int(cache.seq_len[0, 0]) == cache_len_before_step(wl, t_end + 1) - 1
+
+    # ---- the streaming kernel alone, timed with HIP events recorded by the library ------------
+    n_prof = min(args.steps, 64) // E * E or min(args.steps, 64)
+    qp, kp, vp, sp = make_pools(gen, wl, t_end, n_prof, dev)
+    fp = evict_flags(wl, t_end, n_prof)
+    ev = HipEvents(n_prof * L)
+    stream = torch.cuda.current_stream().cuda_stream
+    lens = []
+    for i in range(n_prof):
+        for l in range(L):
+            a, b = ev.pairs[i * L + l]
+            B.dynts_set_kernel_events(cache.ctx, a, b)
+            B.dynts_decode_step(cache.ctx, l, qp[i, l], kp[i, l], vp[i, l], out[l],
+                                s_new=sp[i] if sp is not None else None, stream=stream)
+            B.dynts_set_kernel_events(cache.ctx, None, None)
+            if fp[i]:
+                B.dynts_select_evict(cache.ctx, l, cache.keep_idx, cache.new_len, -1, stream=stream)
+                B.dynts_compact(cache.ctx, l, cache.keep_idx, cache.new_len, stream=stream)
+        lens.append(cache_len_before_step(wl, t_end + 1 + i))
+    torch.cuda.synchronize()
+    k_ms = [ev.elapsed_ms(i) for i in range(n_prof * L)]
+    ev.close()
+    k_avg_ms = sum(k_ms) / len(k_ms)
+    bytes_launch = sum(algorithmic_bytes(wl, [n] * wl.batch, wl.batch) for n in lens) / len(lens)
+    achieved = bytes_launch / (k_avg_ms * 1e-3) / 1e9
+    traffic = None
+    tf = os.path.join(ROOT, "profiles", "attend_partial_%s_traffic.json" % wl.name)
+    if os.path.exists(tf):
+        traffic = json.load(open(tf)).get("hbm_bytes_per_launch")
+    roofline = {"bound": "hbm", "kernel": "attend_partial_kernel<%d,attend,pending,append>" % wl.head_dim,
+                "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": traffic,
+                "kernel_avg_us": round(k_avg_ms * 1e3, 2), "algorithmic_bytes_per_launch": int(bytes_launch),
+                "launches_timed": len(k_ms)}
+    step_bytes = sum(algorithmic_bytes(wl, [cache_len_before_step(wl, t + args.warmup + 1 + i)] * wl.batch,
+                                       wl.batch) for i in range(args.steps)) * L
+    return dict(value=args.steps / dt, ms_per_step=dt / args.steps * 1e3, roofline=roofline,
+                whole_step_gbs=step_bytes / dt / 1e9, seq_steps_per_s=args.steps * wl.batch / dt,
+                evictions_timed=int(ft.sum()), first_timed_step=t + args.warmup + 1)
+
+
+def run_cpu_baseline(wl, budget_s=20.0):
+    """The float64 oracle, as it stands, on the host cores: whole decode steps of the same
+    workload from a generator-made steady state (one layer's worth scaled to all layers)."""
+    import numpy as np
+    import torch
+    from oracle import dynts_oracle as orc
+    from paper_2601_18383_amd import synth
+
+    gen = synth.Synth(wl, "cpu")
+    E = wl.evict_every
+    n0 = wl.steady_len
+    st = gen.steady_state(0, n0)
+    o = orc.OracleLayer(wl.batch, wl.n_q_heads, wl.n_kv_heads, wl.head_dim, wl.capacity, wl.budget, wl.window,
+                        E, external_scores=wl.external_scores)
+    o.K[:, :, :n0] = st["K"].to(torch.float64).numpy()
+    o.V[:, :, :n0] = st["V"].to(torch.float64).numpy()
+    o.S[:, :, :n0] = st["S"].to(torch.float64).numpy()
+    o.pos[:, :, :n0] = st["pos"].numpy()
+    o.seq_len[:] = n0
+    o.n_prompt[:] = wl.prompt
+    o.next_pos[:] = o.pos[:, :, n0 - 1].max(axis=1) + 1
+    o.steps_done[:] = wl.budget + wl.window + E  # a multiple of E: the next trigger is E steps away
+    threads = orc.max_threads()
+    steps = torch.arange(10 ** 5, 10 ** 5 + 4 * E)
+    q = gen.q(0, steps).to(torch.float64).numpy()
+    k, v = gen.kv(0, steps)
+    k, v = k.to(torch.float64).numpy(), v.to(torch.float64).numpy()
+    s = None
+    if wl.external_scores:
+        s = gen.external_scores(steps).unsqueeze(-1).expand(len(steps), wl.batch, wl.n_kv_heads)
+        s = s.to(torch.float64).contiguous().numpy()
+    done, t0 = 0, time.perf_counter()
+    while done < len(steps):
+        o.step(q[done], k[done], v[done], s[done] if s is not None else None)
+        done += 1
+        if time.perf_counter() - t0 > budget_s and done >= 2:
+            break
+    dt = time.perf_counter() - t0
+    layer_steps_per_s = done / dt
+    return {"value": layer_steps_per_s / wl.n_layers, "unit": "decode steps/s", "cores": threads,
+            "kind": "oracle",
+            "sample": "%d whole layer-steps (append+attend+score%s) of %s, full batch, from a synthetic steady "
+                      "state of %d slots, %.1f s; divided by %d layers" %
+                      (done, ", incl. 1 select+compact" if done >= E else "", wl.name, n0, dt, wl.n_layers)}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=512)
+    ap.add_argument("--warmup", type=int, default=64)
+    ap.add_argument("--workload", default="cfg3")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        sys.exit("bench.py measures one MI355X: the decode path shards over sequences and KV heads "
+                 "without communication, and this build runs on a single GPU only (--gpus 1).")
+    from paper_2601_18383_amd import configs
+    wl = configs.get(args.workload)
+    log("host cores: %d; workload %s" % (os.cpu_count(), wl))
+    r = run_gpu(args, wl)
+    cpu = None if args.no_cpu_baseline else run_cpu_baseline(wl)
+    line = {
+        "metric": "decode steps/sec (attn+score+evict), 1 MI355X", "value": round(r["value"], 2),
+        "unit": "decode steps/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": round(r["ms_per_step"], 5), "higher_is_better": True, "scaling": "weak",
+        "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": "%s: %d layer(s), batch %d, %d q / %d kv heads, head_dim %d, prompt %d, budget %d, "
+                               "window %d, evict every %d; steady state, all sequences active" %
+                               (wl.name, wl.n_layers, wl.batch, wl.n_q_heads, wl.n_kv_heads, wl.head_dim, wl.prompt,
+                                wl.budget, wl.window, wl.evict_every),
+                   "first_timed_step": r["first_timed_step"], "evictions_in_window": r["evictions_timed"],
+                   "sequence_steps_per_s": round(r["seq_steps_per_s"], 1),
+                   "whole_step_algorithmic_GBps": round(r["whole_step_gbs"], 1)},
+        "roofline": r["roofline"], "cpu_baseline": cpu,
+    }
+    print(json.dumps(line), flush=True)
+
+
+if __name__ == "__main__":
+    main()

@@ -21,7 +21,7 @@ EXPORTS = [
     "dynts_version", "dynts_strerror", "dynts_create", "dynts_destroy", "dynts_workspace_bytes",
     "dynts_bind", "dynts_prefill", "dynts_append", "dynts_decode_attend", "dynts_update_scores",
     "dynts_decode_attend_update", "dynts_decode_step", "dynts_select_evict", "dynts_compact",
-    "dynts_decode_loop",
+    "dynts_decode_loop", "dynts_set_kernel_events",
 ]
 
 
@@ -56,6 +56,7 @@ def _load():
     lib.dynts_select_evict.argtypes = [vp, i32, vp, i32, vp, i32, vp, vp]
     lib.dynts_compact.argtypes = [vp, i32, vp, vp, i32, vp, vp]
     lib.dynts_decode_loop.argtypes = [vp, i32, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp, vp, vp]
+    lib.dynts_set_kernel_events.argtypes = [vp, vp, vp]
     for name in EXPORTS:
         getattr(lib, name)
     return lib
@@ -184,6 +185,11 @@ def dynts_decode_loop(ctx, n_steps, q, k_new, v_new, out, keep_idx=None, new_len
                                  _ptr(active, torch.uint8), _ptr(evict_steps), _ptr(trigger, torch.uint8),
                                  _ptr(out, torch.float32), out_step_stride, _ptr(keep_idx, torch.int32),
                                  _ptr(new_len, torch.int32), _stream(stream)), "dynts_decode_loop")
+
+
+def dynts_set_kernel_events(ctx, start, stop):
+    """start, stop: raw hipEvent_t handles (ints) or None."""
+    _check(lib.dynts_set_kernel_events(ctx, start, stop), "dynts_set_kernel_events")
 
 
 class Cache:

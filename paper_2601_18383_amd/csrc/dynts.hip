@@ -78,6 +78,7 @@ struct dynts_ctx {
   int32_t *pos = nullptr, *seq_len = nullptr, *next_pos = nullptr, *n_prompt = nullptr, *status = nullptr;
   unsigned char *ws = nullptr;
   std::vector<unsigned char> pending;  // per layer: a score update is owed
+  hipEvent_t ev_start = nullptr, ev_stop = nullptr;
 };
 
 namespace {
@@ -157,8 +158,10 @@ int run_attend(dynts_ctx *ctx, int layer, const uint16_t *q, const uint16_t *k_n
   p.chunk = pl.chunk; p.nsplit = pl.nsplit; p.scale_log2 = ctx->scale_log2;
 
   const dim3 grid(pl.nsplit, c.n_kv_heads, c.batch);
+  if (ctx->ev_start) (void)hipEventRecord(ctx->ev_start, st);
   if (c.head_dim == 128) launch_partial_d<128>(p, grid, st, attend, apply_pending, append);
   else launch_partial_d<64>(p, grid, st, attend, apply_pending, append);
+  if (ctx->ev_stop) (void)hipEventRecord(ctx->ev_stop, st);
   int rc = launch_status();
   if (rc != DYNTS_OK) return rc;
   if (!attend) return DYNTS_OK;
@@ -363,6 +366,14 @@ int dynts_compact(dynts_ctx *ctx, int32_t layer, const uint8_t *trigger, const i
   if (c.head_dim == 128) hipLaunchKernelGGL((dynts::compact_kernel<128>), grid, dim3(dynts::kCompactThreads), 0, st, p);
   else hipLaunchKernelGGL((dynts::compact_kernel<64>), grid, dim3(dynts::kCompactThreads), 0, st, p);
   return launch_status();
+}
+
+int dynts_set_kernel_events(dynts_ctx *ctx, void *start, void *stop) {
+  if (!ctx) return DYNTS_ENULL;
+  if ((start == nullptr) != (stop == nullptr)) return DYNTS_EINVAL;
+  ctx->ev_start = static_cast<hipEvent_t>(start);
+  ctx->ev_stop = static_cast<hipEvent_t>(stop);
+  return DYNTS_OK;
 }
 
 int dynts_decode_loop(dynts_ctx *ctx, int32_t n_steps, const uint16_t *q, const uint16_t *k_new,
