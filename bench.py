@@ -180,10 +180,10 @@ def run_gpu(args, wl):
     bytes_launch = sum(algorithmic_bytes(wl, [n] * wl.batch, wl.batch) for n in lens) / len(lens)
     achieved = bytes_launch / (k_avg_ms * 1e-3) / 1e9
     traffic = None
-    tf = os.path.join(ROOT, "profiles", "attend_partial_%s_traffic.json" % wl.name)
+    tf = os.path.join(ROOT, "profiles", "attend_kernel_%s_traffic.json" % wl.name)
     if os.path.exists(tf):
         traffic = json.load(open(tf)).get("hbm_bytes_per_launch")
-    roofline = {"bound": "hbm", "kernel": "attend_partial_kernel<%d,attend,pending,append>" % wl.head_dim,
+    roofline = {"bound": "hbm", "kernel": "attend_kernel<%d,attend,pending,append>" % wl.head_dim,
                 "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
                 "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": traffic,
                 "kernel_avg_us": round(k_avg_ms * 1e3, 2), "algorithmic_bytes_per_launch": int(bytes_launch),
@@ -247,15 +247,31 @@ def main():
     ap.add_argument("--steps", type=int, default=512)
     ap.add_argument("--warmup", type=int, default=64)
     ap.add_argument("--workload", default="cfg3")
+    ap.add_argument("--layers", type=int, default=0, help="run only this many layers of the workload's stack "
+                    "(a tuning aid; the workload line says so)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--copy-calibration", action="store_true",
+                    help="also run three plain 1 GiB device copies (a kernel of known traffic, for scaling "
+                         "rocprofv3's FETCH_SIZE / WRITE_SIZE counters)")
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py measures one MI355X: the decode path shards over sequences and KV heads "
                  "without communication, and this build runs on a single GPU only (--gpus 1).")
     from paper_2601_18383_amd import configs
     wl = configs.get(args.workload)
+    if args.layers:
+        import dataclasses
+        wl = dataclasses.replace(wl, name="%s[%d of %d layers]" % (wl.name, args.layers, wl.n_layers),
+                                 n_layers=args.layers)
     log("host cores: %d; workload %s" % (os.cpu_count(), wl))
     r = run_gpu(args, wl)
+    if args.copy_calibration:
+        import torch
+        src = torch.ones(1 << 28, dtype=torch.float32, device="cuda:0")
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            dst.copy_(src)
+        torch.cuda.synchronize()
     cpu = None if args.no_cpu_baseline else run_cpu_baseline(wl)
     line = {
         "metric": "decode steps/sec (attn+score+evict), 1 MI355X", "value": round(r["value"], 2),

@@ -163,10 +163,10 @@ int dynts_decode_loop(dynts_ctx *ctx, int32_t n_steps, const uint16_t *q, const 
                       size_t out_step_stride, int32_t *keep_idx, int32_t *new_len, void *stream);
 
 /* Measurement hook: when both are non-NULL hipEvent_t handles (created by the caller with
- * timing enabled), every later attend launch of this context records `start` on its stream
- * right before the streaming kernel (attention partials + deferred score update, the kernel
- * that moves the K/V bytes) and `stop` right after it, so hipEventElapsedTime(start, stop)
- * is that kernel's duration.  Pass NULLs to switch it off. */
+ * timing enabled), every later attend launch of this context attaches them to the dispatch
+ * of its streaming kernel (attention + deferred score update, the kernel that moves the K/V
+ * bytes): `start` is stamped when that kernel begins, `stop` when it ends, so
+ * hipEventElapsedTime(start, stop) is the kernel's own duration.  Pass NULLs to switch it off. */
 int dynts_set_kernel_events(dynts_ctx *ctx, void *start, void *stop);
 
 #ifdef __cplusplus

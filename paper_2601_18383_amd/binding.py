@@ -10,7 +10,7 @@ import os
 import torch
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
-LIB_PATH = os.path.join(_HERE, "libdynts.so")
+LIB_PATH = os.environ.get("DYNTS_LIBRARY") or os.path.join(_HERE, "libdynts.so")  # override: development builds
 
 DYNTS_OK = 0
 DYNTS_EINVAL, DYNTS_ENULL, DYNTS_ESHAPE, DYNTS_ECAPACITY = -1, -2, -3, -4

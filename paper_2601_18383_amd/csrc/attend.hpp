@@ -1,122 +1,192 @@
 // Decode attention + deferred importance-score accumulation for gfx950 (wave64, MFMA).
 //
-// One workgroup (4 waves) owns a contiguous chunk of one (sequence, KV head) cache; each
-// wave walks 32-slot tiles of that chunk on its own:
-//   * K rows go straight from HBM into MFMA A-operand registers (16-byte loads; lane
-//     (r, kg) holds row r, columns 32*ks + 8*kg .. +7), and one v_mfma_f32_16x16x32_bf16
-//     per 32 columns gives the logits of 16 slots x 16 (padded) query heads of the group,
-//     so the K tile is read once for the whole GQA group (Eq. attn-score).
-//   * the same K registers are multiplied with the PREVIOUS step's query; with that step's
-//     final softmax statistics this yields its attention weights exactly, which are summed
-//     over the group and added to S (Eq. importance-score, running form) -- the score
-//     update rides on this step's pass over K instead of a second pass or a logit spill.
+// One workgroup (4 waves) owns a contiguous chunk of one (sequence, KV head) cache; its waves
+// walk the chunk's 32-slot tiles in turn, each wave with the next tile's loads already in
+// flight while it works on the current one:
+//   * K rows go straight from HBM into MFMA operand registers (16-byte loads; lane (r, kg)
+//     holds row r, columns 32*ks + 8*kg .. +7).  One v_mfma_f32_16x16x32_bf16 per 32 columns
+//     gives the logits of 16 slots x 16 (padded) query heads of the group, so a K tile is read
+//     once for the whole GQA group (Eq. attn-score).
+//   * the same K registers are multiplied with the PREVIOUS step's query (operands swapped, so
+//     a lane ends up with 4 heads of one slot); with that step's final softmax statistics this
+//     gives its attention weights exactly, which are summed over the group and added to S
+//     (Eq. importance-score, running form).  The score update thus rides on this step's pass
+//     over K instead of a second pass or a spill of logits.
 //   * V rows are staged through a wave-private LDS tile (coalesced 16-byte loads in,
-//     column reads out) to form the transposed MFMA operand; softmax weights are split
-//     into bf16 hi + lo parts so the P.V product keeps ~16 bits of the weights
-//     (Eq. attn-o), accumulation is fp32 throughout.
-//   * online softmax state (running max, sum, output) is per wave; the four waves are
-//     combined in LDS and one partial per workgroup goes to the workspace; a small merge
-//     kernel combines the splits, writes `out`, and saves the query and the statistics the
-//     next step's score update needs.
+//     ds_read_b64_tr_b16 transposing reads out) to form the V^T MFMA operand; the softmax
+//     weights are split into bf16 hi + lo parts so P.V keeps ~16 bits of each weight
+//     (Eq. attn-o); accumulation is fp32 throughout.
+//   * online-softmax state (running max, sum, output) is per wave; the four waves are combined
+//     in LDS.  A chunk that is the whole cache is finished on the spot; otherwise the partial
+//     goes to the workspace and the LAST workgroup of the (sequence, KV head) to arrive
+//     (device-scope counter) merges the partials, writes `out`, and saves the query and the
+//     statistics that the next step's score update needs.  The last workgroup of a sequence
+//     advances seq_len / next_pos.  No second kernel, no host round trip.
 #pragma once
 #include <hip/hip_runtime.h>
 #include <stdint.h>
+
+#include <type_traits>
 
 namespace dynts {
 
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef float f32x4 __attribute__((ext_vector_type(4)));
+typedef short i16x4 __attribute__((ext_vector_type(4)));
+typedef short i16x8 __attribute__((ext_vector_type(8)));
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 
-constexpr int kWaves = 4;           // waves per workgroup
 constexpr int kTile = 32;           // cache slots one wave handles per iteration
-constexpr int kThreads = kWaves * 64;
-constexpr int kChunkQuantum = kWaves * kTile;  // chunk sizes are multiples of this
+// A workgroup has W waves (4 or 8); chunk sizes are multiples of W * kTile slots.
 
 struct AttendParams {
   uint16_t *K, *V;          // layer base, [Nb][Hkv][cap][D]
   float *S;                 // [Nb][Hkv][cap]
   int32_t *pos;             // [Nb][Hkv][cap]
-  const int32_t *seq_len;   // [Nb]
+  int32_t *seq_len;         // [Nb]
   const int32_t *n_prompt;  // [Nb]
-  const int32_t *next_pos;  // [Nb]
+  int32_t *next_pos;        // [Nb]
   const uint16_t *q;        // [Nb][Hq][D]
   const uint16_t *k_new, *v_new;  // [Nb][Hkv][D] (fused append) or null
   const float *s_new;       // [Nb][Hkv] or null
   const uint8_t *active;    // [Nb] or null
-  const uint16_t *qprev;    // [Nb][Hq][D] query of the deferred update
-  const float *mlprev;      // [Nb][Hq][2] (max in log2 units, sum) of the deferred update
-  const int32_t *nprev;     // [Nb] slots the deferred update covers (0 = none)
+  float *out;               // [Nb][Hq][D]
+  float *lse;               // [Nb][Hq] or null
+  const uint16_t *qprev;    // [Nb][Hq][D] query of the deferred update (read)
+  uint16_t *qnext;          // [Nb][Hq][D] where this call's query is kept for the next deferred update
+  float *mlprev;            // [Nb][Hq][2] (max in log2 units, sum) of the deferred update
+  int32_t *nprev;           // [Nb] slots the deferred update covers (0 = none)
   float *part_o;            // [Nb][Hkv][nsplit][G][D]
   float *part_ml;           // [Nb][Hkv][nsplit][G][2]
-  int32_t *ncur;            // [Nb] slots attended this call (0 = skipped), for the merge
+  uint32_t *unit_cnt;       // [Nb][Hkv] arrival counters, zero between launches
+  uint32_t *seq_cnt;        // [Nb]      arrival counters, zero between launches
   int32_t *status;
   int Nb, Hq, Hkv, G, cap, chunk, nsplit;
+  int track;                // 1: scores are accumulated from attention (save q and statistics)
   float scale_log2;         // softmax scale * log2(e)
+  unsigned long long *trace;  // timestamps per workgroup (builds with -DDYNTS_TRACE only), else null
 };
 
+#ifdef DYNTS_TRACE
+#define DYNTS_STAMP(slot)                                                                         \
+  do {                                                                                           \
+    if (p.trace && threadIdx.x == 0)                                                             \
+      p.trace[(((size_t)blockIdx.z * gridDim.y + blockIdx.y) * gridDim.x + blockIdx.x) * 8 + (slot)] = wall_clock64(); \
+  } while (0)
+#else
+#define DYNTS_STAMP(slot) do {} while (0)
+#endif
+
+__device__ __forceinline__ u32x4 load_u32x4(const uint16_t *p) { return *reinterpret_cast<const u32x4 *>(p); }
+__device__ __forceinline__ void store_u32x4(uint16_t *p, u32x4 v) { *reinterpret_cast<u32x4 *>(p) = v; }
 __device__ __forceinline__ bf16x8 load_bf16x8(const uint16_t *p) {
-  return __builtin_bit_cast(bf16x8, *reinterpret_cast<const uint4 *>(p));
+  return __builtin_bit_cast(bf16x8, load_u32x4(p));
 }
 __device__ __forceinline__ void store_bf16x8(uint16_t *p, bf16x8 v) {
-  *reinterpret_cast<uint4 *>(p) = __builtin_bit_cast(uint4, v);
+  store_u32x4(p, __builtin_bit_cast(u32x4, v));
 }
 
-template <int D, bool ATTEND, bool PENDING, bool APPEND>
-__global__ __launch_bounds__(kThreads) void attend_partial_kernel(const AttendParams p) {
+// K rows of the 32-slot tile at t as MFMA operand fragments; rows past n_vis repeat the last row
+template <int D>
+__device__ __forceinline__ void load_k_tile(bf16x8 (&kf)[2][D / 32], const uint16_t *Kb, int t, int r16, int kg,
+                                            int n_vis) {
+#pragma unroll
+  for (int s = 0; s < 2; ++s) {
+    int row = t + 16 * s + r16;
+    row = row < n_vis ? row : n_vis - 1;
+    const uint16_t *src = Kb + (size_t)row * D + 8 * kg;
+#pragma unroll
+    for (int ks = 0; ks < D / 32; ++ks) kf[s][ks] = load_bf16x8(src + 32 * ks);
+  }
+}
+
+// V rows of the tile, whole rows across 16-byte pieces (coalesced); rows past n_now repeat the last row
+template <int D>
+__device__ __forceinline__ void load_v_tile(u32x4 (&vf)[kTile / (64 / (D / 8))], const uint16_t *Vb, int t,
+                                            int lane, int n_now) {
+  constexpr int PIECES = D / 8, VROWS = 64 / PIECES;
+#pragma unroll
+  for (int it = 0; it < kTile / VROWS; ++it) {
+    int row = t + VROWS * it + lane / PIECES;
+    row = row < n_now ? row : n_now - 1;
+    vf[it] = load_u32x4(Vb + (size_t)row * D + 8 * (lane % PIECES));
+  }
+}
+// Cross-workgroup traffic inside one launch (split partials, arrival counters) goes through
+// device-coherent accesses: relaxed agent-scope atomics compile to sc1 loads/stores that are
+// written through to, and read from, the level all XCDs share.  A store counts as complete
+// (vmcnt) only once it is visible there, so "wait for my stores, then bump the counter"
+// orders them without a cache-wide write-back/invalidate fence.
+__device__ __forceinline__ void coherent_store(float *p, float v) {
+  __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ __forceinline__ float coherent_load(const float *p) {
+  return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ __forceinline__ void wait_own_stores() { __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup"); }
+
+__device__ __forceinline__ void wave_lds_fence() {
+  __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+  __builtin_amdgcn_wave_barrier();
+  __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+}
+
+template <int D, int W, bool ATTEND, bool PENDING, bool APPEND>
+__global__ __launch_bounds__(W * 64, 2) void attend_kernel(const AttendParams p) {
+  constexpr int kWaves = W, kThreads = W * 64, kChunkQuantum = W * kTile;
   constexpr int KS = D / 32;              // MFMA k-steps per K row
   constexpr int CB = D / 16;              // 16-column blocks of the output
   constexpr int PIECES = D / 8;           // 16-byte pieces per row
   constexpr int VROWS = 64 / PIECES;      // rows covered by one wave-wide 16-byte load
   constexpr int VIT = kTile / VROWS;
-  constexpr int VSTRIDE = 2 * D + 8;      // bytes per staged V row (+8: column reads hit distinct banks)
+  constexpr int VSTRIDE = 2 * D + 32;     // bytes per staged V row (+32: transposing reads hit distinct banks)
   constexpr int OSTRIDE = D + 4;          // floats per row of the cross-wave output reduction
-  static_assert(kWaves * kTile * VSTRIDE == 64 * OSTRIDE * 4, "LDS tile is reused for the reduction");
+  static_assert(kWaves * kTile * VSTRIDE >= kWaves * 16 * OSTRIDE * 4, "LDS tile is reused for the reduction");
   __shared__ __align__(16) unsigned char smem[kWaves * kTile * VSTRIDE];
   __shared__ float sm_m[kWaves][16];
   __shared__ float sm_l[kWaves][16];
+  __shared__ float sm_fin[2][16];
+  __shared__ uint32_t sm_flag;
 
+  DYNTS_STAMP(0);
   const int tid = threadIdx.x;
   const int lane = tid & 63, wave = tid >> 6;
-  const int r16 = lane & 15, kg = lane >> 4;  // r16: row within a 16-slot sub-tile == query head index g
-  const int g = r16;
+  const int r16 = lane & 15, kg = lane >> 4;
+  const int g = r16;  // query head (within the group) of this lane's logits
   const int split = blockIdx.x, h = blockIdx.y, b = blockIdx.z;
   const int G = p.G;
-
-  const bool act = p.active ? (p.active[b] != 0) : true;
-  int n_old = p.seq_len[b];
-  n_old = n_old < 0 ? 0 : (n_old > p.cap ? p.cap : n_old);
-  int n_now = 0;
-  bool appending = false;
-  if (ATTEND && act) {
-    if (APPEND) {
-      if (n_old < p.cap) {
-        n_now = n_old + 1;
-        appending = true;
-      } else if (tid == 0 && split == 0 && h == 0) {
-        atomicOr(p.status, 1);
-      }
-    } else {
-      n_now = n_old;
-    }
-  }
-  int n_prev = PENDING ? p.nprev[b] : 0;
-  n_prev = n_prev < 0 ? 0 : (n_prev > p.cap ? p.cap : n_prev);
-  const int M = p.n_prompt[b];
-  const int n_vis = n_now > n_prev ? n_now : n_prev;
-  if (ATTEND && tid == 0 && split == 0 && h == 0) p.ncur[b] = n_now;
-
-  const int r0 = split * p.chunk;
-  const int r1 = (r0 + p.chunk < n_vis) ? r0 + p.chunk : n_vis;
-  if (r0 >= r1) return;
 
   const size_t unit = (size_t)b * p.Hkv + h;
   uint16_t *Kb = p.K + unit * (size_t)p.cap * D;
   uint16_t *Vb = p.V + unit * (size_t)p.cap * D;
   float *Sb = p.S + unit * (size_t)p.cap;
-  const uint16_t *knew = APPEND ? p.k_new + unit * D : nullptr;
-  const uint16_t *vnew = APPEND ? p.v_new + unit * D : nullptr;
+  unsigned char *vst = smem + wave * (kTile * VSTRIDE);
+  const int vrow_l = lane / PIECES, vpiece = lane % PIECES;
+  const int r0 = split * p.chunk;
+  int t = r0 + kTile * wave;
 
-  // query fragments (MFMA B operand): lane (g, kg) holds q[g][32*ks + 8*kg .. +7]
+  // ---- request everything the prologue needs in one go -----------------------------------
+  // Loads return in order, so the few scalars (lengths, activity) go first; right behind them
+  // the first tile, whose addresses depend on kernel arguments only (rows clamped to the end
+  // of the allocation; what lies past the sequence is masked once its length is known); then
+  // the query and the statistics.
+  const int act_raw = p.active ? (int)p.active[b] : 1;
+  const int len_raw = p.seq_len[b];
+  const int prev_raw = PENDING ? p.nprev[b] : 0;
+  const int M = p.n_prompt[b];
+  __builtin_amdgcn_sched_barrier(0);
+  bf16x8 kf[2][KS];
+  u32x4 vf[VIT];
+  float s_old = 0.f;
+  load_k_tile<D>(kf, Kb, t, r16, kg, p.cap);
+  if (PENDING) {
+    const int tok = t + (lane & (kTile - 1));
+    s_old = Sb[tok < p.cap ? tok : p.cap - 1];
+  }
+  if (ATTEND) load_v_tile<D>(vf, Vb, t, lane, p.cap);
+  __builtin_amdgcn_sched_barrier(0);
+
+  // query fragments: lane (g, kg) holds q[g][32*ks + 8*kg .. +7]
   bf16x8 qf[KS], qpf[KS];
   const size_t qoff = ((size_t)b * p.Hq + (size_t)h * G + g) * D + 8 * kg;
 #pragma unroll
@@ -128,11 +198,99 @@ __global__ __launch_bounds__(kThreads) void attend_partial_kernel(const AttendPa
       if (PENDING) qpf[ks] = load_bf16x8(p.qprev + qoff + 32 * ks);
     }
   }
-  float mprev = 0.f, inv_lprev = 0.f;
-  if (PENDING && g < G && n_prev > 0) {
-    const float *ml = p.mlprev + ((size_t)b * p.Hq + (size_t)h * G + g) * 2;
-    mprev = ml[0];
-    inv_lprev = 1.0f / ml[1];
+  // statistics of the deferred update for heads 4*kg .. 4*kg+3 (the rows this lane gets from
+  // the swapped-operand MFMA)
+  float mprev[4], inv_lprev[4];
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    mprev[i] = 0.f;
+    inv_lprev[i] = 0.f;
+    const int gg = 4 * kg + i;
+    if (PENDING && gg < G) {
+      const float *ml = p.mlprev + ((size_t)b * p.Hq + (size_t)h * G + gg) * 2;
+      mprev[i] = ml[0];
+      inv_lprev[i] = ml[1];
+    }
+  }
+
+  // the wave that takes the appended token asks for its row (and what goes with it) right away
+  const bool new_wave = APPEND && split == 0 && wave == 0;
+  bf16x8 kn[KS];
+  uint2 vn[CB];
+  int pos_new = 0;
+  float s_init = 0.f;
+  if (new_wave) {
+    const uint16_t *knew = p.k_new + unit * D;
+    const uint16_t *vnew = p.v_new + unit * D;
+#pragma unroll
+    for (int ks = 0; ks < KS; ++ks) kn[ks] = load_bf16x8(knew + 32 * ks + 8 * kg);  // every operand row is k_new
+#pragma unroll
+    for (int cb = 0; cb < CB; ++cb) vn[cb] = *reinterpret_cast<const uint2 *>(vnew + 16 * cb + 4 * kg);
+    pos_new = p.next_pos[b];
+    if (p.s_new) s_init = p.s_new[unit];
+  }
+
+  // ---- what this launch does for sequence b (identical in every workgroup of b) ---------
+  // n_rows cache slots are attended from the cache; when a token is appended in the same
+  // pass its row is taken from k_new / v_new up front (below), so the tiles never see it.
+  const bool act = act_raw != 0;
+  int n_old = len_raw;
+  n_old = n_old < 0 ? 0 : (n_old > p.cap ? p.cap : n_old);
+  int n_now = 0, n_rows = 0;
+  bool appending = false;
+  if (ATTEND && act) {
+    if (APPEND) {
+      if (n_old < p.cap) {
+        n_now = n_old + 1;
+        n_rows = n_old;
+        appending = true;
+      } else if (tid == 0 && split == 0 && h == 0) {
+        atomicOr(p.status, 1);
+      }
+    } else {
+      n_now = n_rows = n_old;
+    }
+  }
+  int n_prev = prev_raw;
+  n_prev = n_prev < 0 ? 0 : (n_prev > p.cap ? p.cap : n_prev);
+  const int n_vis = n_rows > n_prev ? n_rows : n_prev;
+  // workgroups of this unit that produce an attention partial (chunk 0 always does when the
+  // sequence is attended: it owns the appended token), and that have any work at all
+  const int chunks_now = n_now > 0 ? ((n_rows + p.chunk - 1) / p.chunk > 1 ? (n_rows + p.chunk - 1) / p.chunk : 1) : 0;
+  const int chunks_prev = (n_prev + p.chunk - 1) / p.chunk;
+  const int chunks_vis = chunks_now > chunks_prev ? chunks_now : chunks_prev;
+#pragma unroll
+  for (int i = 0; i < 4; ++i)  // inv_l = 0 switches padded heads and idle sequences off
+    inv_lprev[i] = (PENDING && 4 * kg + i < G && n_prev > 0) ? 1.0f / inv_lprev[i] : 0.f;
+
+  // Every workgroup of the sequence checks in once it no longer needs seq_len / nprev; the
+  // last one advances them.  (A workgroup without work checks in right away.)
+  auto seq_checkin = [&]() {
+    if (!ATTEND) return;
+    if (tid == 0) {
+      const uint32_t total = (uint32_t)p.nsplit * p.Hkv;
+      if (atomicAdd(&p.seq_cnt[b], 1u) == total - 1) {
+        __hip_atomic_store(&p.seq_cnt[b], 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        if (p.track) p.nprev[b] = n_now;
+        if (APPEND && appending) {
+          p.seq_len[b] = n_now;
+          p.next_pos[b] += 1;
+        }
+      }
+    }
+  };
+
+  if (split >= chunks_vis) {
+    seq_checkin();
+    return;
+  }
+  const int r1 = (r0 + p.chunk < n_vis) ? r0 + p.chunk : n_vis;
+
+  // keep this call's query for the next deferred score update (its own buffer: the old one is
+  // still being read by the other workgroups of this launch)
+  if (ATTEND && p.track && split == 0 && wave == 0 && g < G && n_now > 0) {
+#pragma unroll
+    for (int ks = 0; ks < KS; ++ks) store_bf16x8(p.qnext + qoff + 32 * ks, qf[ks]);
   }
 
   float m_run = -INFINITY, l_run = 0.f;
@@ -140,146 +298,168 @@ __global__ __launch_bounds__(kThreads) void attend_partial_kernel(const AttendPa
 #pragma unroll
   for (int cb = 0; cb < CB; ++cb) oacc[cb] = f32x4{0.f, 0.f, 0.f, 0.f};
 
-  unsigned char *vst = smem + wave * (kTile * VSTRIDE);
+  // ---- fused append: the new token is this wave's starting softmax state -----------------
+  // One wave of the unit takes the appended token: its logit is q.k_new for every head, its
+  // weight relative to itself is 1, so the running state starts as (max = logit, sum = 1,
+  // output = v_new).  The same wave writes the row into the cache.  All of it overlaps the
+  // wait for the first tile.
+  if (new_wave && appending) {
+    f32x4 a0 = f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+    for (int ks = 0; ks < KS; ++ks) a0 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kn[ks], qf[ks], a0, 0, 0, 0);
+    m_run = a0[0] * p.scale_log2;
+    l_run = kg == 0 ? 1.f : 0.f;  // per-lane partial sums are added over kg at the end
+#pragma unroll
+    for (int cb = 0; cb < CB; ++cb) {
+      typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
+      const bf16x4 v4 = __builtin_bit_cast(bf16x4, vn[cb]);
+      oacc[cb] = f32x4{(float)v4[0], (float)v4[1], (float)v4[2], (float)v4[3]};
+    }
+    if (r16 == 0) {
+#pragma unroll
+      for (int cb = 0; cb < CB; ++cb) *reinterpret_cast<uint2 *>(Vb + (size_t)n_old * D + 16 * cb + 4 * kg) = vn[cb];
+#pragma unroll
+      for (int ks = 0; ks < KS; ++ks) store_bf16x8(Kb + (size_t)n_old * D + 32 * ks + 8 * kg, kn[ks]);
+    }
+    if (lane == 0) {
+      Sb[n_old] = s_init;
+      p.pos[unit * (size_t)p.cap + n_old] = pos_new;
+    }
+  }
 
-  for (int t = r0 + kTile * wave; t < r1; t += kChunkQuantum) {
-    const bool tile_att = ATTEND && t < n_now;  // wave-uniform
-    // ---- loads --------------------------------------------------------------------
-    bf16x8 kf[2][KS];
+  // the first tile was fetched before the length was known: keep rows past it out of P.V
+  if (ATTEND && t + kTile > n_rows) {
+#pragma unroll
+    for (int it = 0; it < VIT; ++it) vf[it] = (t + VROWS * it + vrow_l < n_rows) ? vf[it] : u32x4{0u, 0u, 0u, 0u};
+  }
+  const int k_last = n_vis > 0 ? n_vis : 1;   // row clamps of the prefetches (always a valid row)
+  const int v_last = n_rows > 0 ? n_rows : 1;
+
+  // ---- one 32-slot tile of this wave -------------------------------------------------------
+  // Branch-free apart from two wave-uniform guards; the next tile's loads are issued
+  // unconditionally (clamped), so the loop never drains its outstanding loads.
+  auto tile = [&](int t) {
+    const int tn = t + kChunkQuantum;
+
+    // logits for the current query (A = K rows, B = q) and for the previous one (swapped:
+    // accp[s][i] = logit(slot t + 16 s + r16, head 4 kg + i))
+    f32x4 acc[2], accp[2];
 #pragma unroll
     for (int s = 0; s < 2; ++s) {
-      int row = t + 16 * s + r16;
-      int rowc = row < n_vis ? row : n_vis - 1;
-      const uint16_t *src = (APPEND && appending && rowc == n_old) ? knew : Kb + (size_t)rowc * D;
+      acc[s] = f32x4{0.f, 0.f, 0.f, 0.f};
+      accp[s] = f32x4{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-      for (int ks = 0; ks < KS; ++ks) kf[s][ks] = load_bf16x8(src + 32 * ks + 8 * kg);
-      if (APPEND && appending && row == n_old) {
-#pragma unroll
-        for (int ks = 0; ks < KS; ++ks) store_bf16x8(Kb + (size_t)n_old * D + 32 * ks + 8 * kg, kf[s][ks]);
+      for (int ks = 0; ks < KS; ++ks) {
+        if (ATTEND) acc[s] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kf[s][ks], qf[ks], acc[s], 0, 0, 0);
+        if (PENDING) accp[s] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(qpf[ks], kf[s][ks], accp[s], 0, 0, 0);
       }
     }
-    uint4 vf[VIT];
-    if (tile_att) {
-#pragma unroll
-      for (int it = 0; it < VIT; ++it) {
-        int row = t + VROWS * it + lane / PIECES;
-        int rowc = row < n_now ? row : n_now - 1;
-        const uint16_t *src = (APPEND && appending && rowc == n_old) ? vnew : Vb + (size_t)rowc * D;
-        vf[it] = *reinterpret_cast<const uint4 *>(src + 8 * (lane % PIECES));
-        if (APPEND && appending && row == n_old)
-          *reinterpret_cast<uint4 *>(Vb + (size_t)n_old * D + 8 * (lane % PIECES)) = vf[it];
-      }
-    }
-    if (APPEND && appending && lane == 0 && t <= n_old && n_old < t + kTile) {
-      Sb[n_old] = p.s_new ? p.s_new[unit] : 0.f;
-      p.pos[unit * (size_t)p.cap + n_old] = p.next_pos[b];
+    const float s_cur = s_old;
+    load_k_tile<D>(kf, Kb, tn, r16, kg, k_last);
+    if (PENDING) {
+      const int tok = tn + (lane & (kTile - 1));
+      s_old = Sb[tok < p.cap ? tok : p.cap - 1];
     }
 
-    // ---- deferred score update: weights of the previous query on these slots -------
+    // ---- deferred score update: S[slot] += sum over the group of alpha_prev[g][slot] --------
     if (PENDING && t < n_prev) {
-      f32x4 accp[2];
+      float part[2];
 #pragma unroll
       for (int s = 0; s < 2; ++s) {
-        accp[s] = f32x4{0.f, 0.f, 0.f, 0.f};
+        float a = 0.f;
 #pragma unroll
-        for (int ks = 0; ks < KS; ++ks)
-          accp[s] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kf[s][ks], qpf[ks], accp[s], 0, 0, 0);
+        for (int i = 0; i < 4; ++i) a += exp2f(accp[s][i] * p.scale_log2 - mprev[i]) * inv_lprev[i];
+        if (G > 4) a += __shfl_xor(a, 16);
+        if (G > 8) a += __shfl_xor(a, 32);
+        part[s] = a;
       }
-      float mine = 0.f;
-#pragma unroll
-      for (int s = 0; s < 2; ++s) {
-#pragma unroll
-        for (int i = 0; i < 4; ++i) {
-          float a = (g < G) ? exp2f(accp[s][i] * p.scale_log2 - mprev) * inv_lprev : 0.f;
-          a += __shfl_xor(a, 1);
-          a += __shfl_xor(a, 2);
-          a += __shfl_xor(a, 4);
-          a += __shfl_xor(a, 8);
-          if (r16 == 4 * s + i) mine = a;
-        }
+      if (G <= 8) {  // lanes of row group 0 (and 1) hold the sums; hand sub-tile 1 to row group 1
+        const float other = __shfl(part[1], r16);
+        if (kg == 1) part[1] = other;
       }
-      if (r16 < 8) {
-        int tok = t + 16 * (r16 >> 2) + 4 * kg + (r16 & 3);
-        if (tok < n_prev && tok >= M) Sb[tok] += mine;
-      }
+      const int tok = t + lane;  // lane < 32: slot of sub-tile kg, row r16
+      if (lane < kTile && tok < n_prev && tok >= M) Sb[tok] = s_cur + (kg == 0 ? part[0] : part[1]);
     }
 
-    // ---- attention for the current query -----------------------------------------
-    if (tile_att) {
-      f32x4 acc[2];
-#pragma unroll
-      for (int s = 0; s < 2; ++s) {
-        acc[s] = f32x4{0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-        for (int ks = 0; ks < KS; ++ks)
-          acc[s] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kf[s][ks], qf[ks], acc[s], 0, 0, 0);
-      }
+    // ---- attention for the current query --------------------------------------------------
+    if (ATTEND && t < n_rows) {
       // acc[s][i] = logit(slot t + 16 s + 4 kg + i, head g)
       float x[8];
       float mx = -INFINITY;
 #pragma unroll
       for (int e = 0; e < 8; ++e) {
-        int tok = t + 16 * (e >> 2) + 4 * kg + (e & 3);
-        x[e] = tok < n_now ? acc[e >> 2][e & 3] * p.scale_log2 : -INFINITY;
+        const int tok = t + 16 * (e >> 2) + 4 * kg + (e & 3);
+        x[e] = tok < n_rows ? acc[e >> 2][e & 3] * p.scale_log2 : -INFINITY;
         mx = fmaxf(mx, x[e]);
       }
       mx = fmaxf(mx, __shfl_xor(mx, 16));
       mx = fmaxf(mx, __shfl_xor(mx, 32));
-      const float m_new = fmaxf(m_run, mx);  // finite: the tile holds at least one valid slot
+      const float m_new = fmaxf(m_run, mx);     // finite: the tile holds at least one valid slot
       const float corr = exp2f(m_run - m_new);  // m_run = -inf on the first tile -> 0
       m_run = m_new;
       bf16x8 ph, pl;
       float psum = 0.f;
 #pragma unroll
       for (int e = 0; e < 8; ++e) {
-        float pe = exp2f(x[e] - m_new);
+        const float pe = exp2f(x[e] - m_new);
         psum += pe;
-        __bf16 hi = (__bf16)pe;
+        const __bf16 hi = (__bf16)pe;
         ph[e] = hi;
         pl[e] = (__bf16)(pe - (float)hi);
       }
       l_run = l_run * corr + psum;
-      if (__any(corr != 1.0f)) {
 #pragma unroll
-        for (int cb = 0; cb < CB; ++cb) oacc[cb] *= corr;
-      }
-      // stage V rows: the wave's own tile, read back column-wise below
+      for (int cb = 0; cb < CB; ++cb) oacc[cb] *= corr;
+      // stage this tile's V rows in the wave's LDS tile, then fetch the next tile's
 #pragma unroll
-      for (int it = 0; it < VIT; ++it) {
-        unsigned char *dst = vst + (VROWS * it + lane / PIECES) * VSTRIDE + 16 * (lane % PIECES);
-        *reinterpret_cast<uint2 *>(dst) = make_uint2(vf[it].x, vf[it].y);
-        *reinterpret_cast<uint2 *>(dst + 8) = make_uint2(vf[it].z, vf[it].w);
-      }
-      __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-      __builtin_amdgcn_wave_barrier();
-      __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+      for (int it = 0; it < VIT; ++it)
+        *reinterpret_cast<u32x4 *>(vst + (VROWS * it + vrow_l) * VSTRIDE + 16 * vpiece) = vf[it];
+      wave_lds_fence();
+      load_v_tile<D>(vf, Vb, tn, lane, v_last);
 #pragma unroll
       for (int cb = 0; cb < CB; ++cb) {
-        // V^T operand: lane (c = 16 cb + r16, kg) holds V[t + 16 s + 4 kg + i][c] in element 4 s + i
-        uint32_t w[4];
-#pragma unroll
-        for (int e2 = 0; e2 < 4; ++e2) {
-          int ea = 2 * e2, eb = 2 * e2 + 1;
-          int rowa = 16 * (ea >> 2) + 4 * kg + (ea & 3);
-          int rowb = 16 * (eb >> 2) + 4 * kg + (eb & 3);
-          uint32_t lo = *reinterpret_cast<const uint16_t *>(vst + rowa * VSTRIDE + 2 * (16 * cb + r16));
-          uint32_t hi = *reinterpret_cast<const uint16_t *>(vst + rowb * VSTRIDE + 2 * (16 * cb + r16));
-          w[e2] = lo | (hi << 16);
-        }
-        bf16x8 vt = __builtin_bit_cast(bf16x8, make_uint4(w[0], w[1], w[2], w[3]));
+        // V^T operand: lane (c = 16 cb + r16, kg) gets V[t + 16 s + 4 kg + i][c] as element 4 s + i.
+        // ds_read_b64_tr_b16: within 16 lanes, lane i's element e comes from source lane
+        // 4 e + i/4, element i%4; so source lane j points at row (j / 4), columns 4 (j % 4) .. +3.
+        const unsigned char *src = vst + (4 * kg + (r16 >> 2)) * VSTRIDE + 2 * (16 * cb + 4 * (r16 & 3));
+        i16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
+            (__attribute__((address_space(3))) i16x4 *)(src));
+        i16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
+            (__attribute__((address_space(3))) i16x4 *)(src + 16 * VSTRIDE));
+        i16x8 both = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+        const bf16x8 vt = __builtin_bit_cast(bf16x8, both);
         oacc[cb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(vt, ph, oacc[cb], 0, 0, 0);
         oacc[cb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(vt, pl, oacc[cb], 0, 0, 0);
       }
-      __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-      __builtin_amdgcn_wave_barrier();
-      __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+      wave_lds_fence();
     }
-  }
+  };
+
+  DYNTS_STAMP(1);
+#ifdef DYNTS_TRACE
+  __builtin_amdgcn_s_waitcnt(0);  // development: when has everything the prologue asked for arrived
+  DYNTS_STAMP(2);
+#endif
+  for (; t < r1; t += kChunkQuantum) tile(t);
+  DYNTS_STAMP(3);
+  DYNTS_STAMP(4);
+#ifdef DYNTS_TRACE_WAVES  // development: when each wave left its tile loop (overwrites the phase stamps)
+  if (p.trace && lane == 0)
+    p.trace[(((size_t)blockIdx.z * gridDim.y + blockIdx.y) * gridDim.x + blockIdx.x) * 8 + (wave & 7)] = wall_clock64();
+  __syncthreads();
+  return;
+#endif
 
   if (!ATTEND) return;
-  if (r0 >= n_now) return;  // chunk only carried a deferred update (workgroup-uniform)
+  const bool has_partial = split < chunks_now;  // workgroup-uniform; false: the chunk only carried a deferred update
+  if (chunks_vis == 1 && !has_partial) {
+    seq_checkin();
+    return;
+  }
 
-  // ---- combine the four waves, emit one partial per workgroup ------------------------
+  // ---- combine the four waves ------------------------------------------------------------
+  float *ored = reinterpret_cast<float *>(smem);
+  if (has_partial) {
   l_run += __shfl_xor(l_run, 16);
   l_run += __shfl_xor(l_run, 32);
   if (kg == 0) {
@@ -291,22 +471,12 @@ __global__ __launch_bounds__(kThreads) void attend_partial_kernel(const AttendPa
 #pragma unroll
   for (int w = 1; w < kWaves; ++w) mstar = fmaxf(mstar, sm_m[w][g]);
   const float f = (m_run == -INFINITY) ? 0.f : exp2f(m_run - mstar);
-  float *ored = reinterpret_cast<float *>(smem);
   if (g < G) {
 #pragma unroll
     for (int cb = 0; cb < CB; ++cb) {
       f32x4 v = oacc[cb] * f;
       *reinterpret_cast<f32x4 *>(ored + (wave * 16 + g) * OSTRIDE + 16 * cb + 4 * kg) = v;
     }
-  }
-  __syncthreads();
-  const size_t pbase = (unit * p.nsplit + split) * (size_t)G;
-  for (int idx = tid; idx < G * D; idx += kThreads) {
-    int gg = idx / D, c = idx % D;
-    float sum = 0.f;
-#pragma unroll
-    for (int w = 0; w < kWaves; ++w) sum += ored[(w * 16 + gg) * OSTRIDE + c];
-    p.part_o[(pbase + gg) * D + c] = sum;
   }
   if (tid < G) {
     float ms = sm_m[0][tid];
@@ -315,63 +485,125 @@ __global__ __launch_bounds__(kThreads) void attend_partial_kernel(const AttendPa
     float ls = 0.f;
 #pragma unroll
     for (int w = 0; w < kWaves; ++w) {
-      float mw = sm_m[w][tid];
+      const float mw = sm_m[w][tid];
       ls += (mw == -INFINITY) ? 0.f : sm_l[w][tid] * exp2f(mw - ms);
     }
-    p.part_ml[(pbase + tid) * 2 + 0] = ms;
-    p.part_ml[(pbase + tid) * 2 + 1] = ls;
+    sm_fin[0][tid] = ms;
+    sm_fin[1][tid] = ls;
   }
-}
+  __syncthreads();
+  }
 
-struct MergeParams {
-  const float *part_o, *part_ml;
-  const int32_t *ncur;      // [Nb]
-  const uint16_t *q;        // [Nb][Hq][D]
-  float *out;               // [Nb][Hq][D]
-  float *lse;               // [Nb][Hq] or null
-  uint16_t *qprev;          // [Nb][Hq][D] or null (no score bookkeeping)
-  float *mlprev;            // [Nb][Hq][2]
-  int32_t *nprev;           // [Nb]
-  int32_t *seq_len, *next_pos;  // [Nb]; advanced when the step appended
-  int Hq, Hkv, G, chunk, nsplit, appended;
-};
-
-// grid (Hq, Nb), block D threads: combine the split partials of one query head.
-template <int D>
-__global__ __launch_bounds__(D) void attend_merge_kernel(const MergeParams p) {
-  const int hq = blockIdx.x, b = blockIdx.y, c = threadIdx.x;
-  const int h = hq / p.G, gg = hq % p.G;
-  const int n_now = p.ncur[b];
-  if (n_now > 0) {
-    const int ns = (n_now + p.chunk - 1) / p.chunk;
-    const size_t base = (((size_t)b * p.Hkv + h) * p.nsplit) * p.G + gg;
-    float m = -INFINITY;
-    for (int s = 0; s < ns; ++s) m = fmaxf(m, p.part_ml[(base + (size_t)s * p.G) * 2]);
-    float L = 0.f, o = 0.f;
-    for (int s = 0; s < ns; ++s) {
-      const size_t row = base + (size_t)s * p.G;
-      float w = exp2f(p.part_ml[row * 2] - m);
-      L += p.part_ml[row * 2 + 1] * w;
-      o += p.part_o[row * D + c] * w;
+  const size_t orow0 = (size_t)b * p.Hq + (size_t)h * G;  // first query head of this group
+  if (chunks_vis == 1) {
+    // the chunk is the whole cache: finish here
+    for (int idx = tid; idx < G * D; idx += kThreads) {
+      const int gg = idx / D, c = idx % D;
+      float sum = 0.f;
+#pragma unroll
+      for (int w = 0; w < kWaves; ++w) sum += ored[(w * 16 + gg) * OSTRIDE + c];
+      p.out[(orow0 + gg) * D + c] = sum / sm_fin[1][gg];
     }
-    const size_t orow = (size_t)b * p.Hq + hq;
-    p.out[orow * D + c] = o / L;
-    if (p.lse && c == 0) p.lse[orow] = (m + log2f(L)) * 0.6931471805599453f;
-    if (p.qprev) {
-      p.qprev[orow * D + c] = p.q[orow * D + c];
-      if (c == 0) {
-        p.mlprev[orow * 2] = m;
-        p.mlprev[orow * 2 + 1] = L;
+    if (tid < G) {
+      if (p.lse) p.lse[orow0 + tid] = (sm_fin[0][tid] + log2f(sm_fin[1][tid])) * 0.6931471805599453f;
+      if (p.track) {
+        p.mlprev[(orow0 + tid) * 2] = sm_fin[0][tid];
+        p.mlprev[(orow0 + tid) * 2 + 1] = sm_fin[1][tid];
+      }
+    }
+    DYNTS_STAMP(7);
+    seq_checkin();
+    return;
+  }
+
+  // ---- several chunks: publish the partial, the last arrival merges ---------------------------
+  if (has_partial) {
+    const size_t pbase = (unit * p.nsplit + split) * (size_t)G;
+    for (int idx = tid; idx < G * D; idx += kThreads) {
+      const int gg = idx / D, c = idx % D;
+      float sum = 0.f;
+#pragma unroll
+      for (int w = 0; w < kWaves; ++w) sum += ored[(w * 16 + gg) * OSTRIDE + c];
+      coherent_store(&p.part_o[(pbase + gg) * D + c], sum);
+    }
+    if (tid < G) {
+      coherent_store(&p.part_ml[(pbase + tid) * 2 + 0], sm_fin[0][tid]);
+      coherent_store(&p.part_ml[(pbase + tid) * 2 + 1], sm_fin[1][tid]);
+    }
+  }
+  wait_own_stores();
+  __syncthreads();
+  DYNTS_STAMP(5);
+  if (tid == 0) sm_flag = atomicAdd(&p.unit_cnt[unit], 1u);
+  __syncthreads();
+  DYNTS_STAMP(6);
+  if (sm_flag == (uint32_t)chunks_vis - 1 && tid == 0)
+    __hip_atomic_store(&p.unit_cnt[unit], 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+  if (sm_flag == (uint32_t)chunks_vis - 1 && chunks_now > 0) {
+    // every thread merges its own output elements; the partials of up to four chunks are
+    // requested together so the merge costs one trip to the coherent level, not one per chunk
+    const size_t ubase = unit * p.nsplit * (size_t)G;
+    constexpr int NE = (16 * D + kThreads - 1) / kThreads;  // output elements per thread at the largest group size
+    const int ne = (G * D + kThreads - 1) / kThreads;
+    float m_e[NE], L_e[NE], o_e[NE];
+#pragma unroll
+    for (int k = 0; k < NE; ++k) {
+      m_e[k] = -INFINITY;
+      L_e[k] = 0.f;
+      o_e[k] = 0.f;
+    }
+    for (int s0 = 0; s0 < chunks_now; s0 += 4) {
+      float ms[NE][4], ls[NE][4], os[NE][4];
+#pragma unroll
+      for (int k = 0; k < NE; ++k) {
+        if (k < ne) {
+          int idx = tid + k * kThreads;
+          idx = idx < G * D ? idx : G * D - 1;
+          const int gg = idx / D, c = idx % D;
+#pragma unroll
+          for (int j = 0; j < 4; ++j) {
+            const int sj = s0 + j < chunks_now ? s0 + j : chunks_now - 1;
+            const size_t row = ubase + (size_t)sj * G + gg;
+            ms[k][j] = coherent_load(&p.part_ml[row * 2]);
+            ls[k][j] = coherent_load(&p.part_ml[row * 2 + 1]);
+            os[k][j] = coherent_load(&p.part_o[row * D + c]);
+          }
+        }
+      }
+#pragma unroll
+      for (int k = 0; k < NE; ++k) {
+        if (k < ne) {
+#pragma unroll
+          for (int j = 0; j < 4; ++j) {
+            if (s0 + j < chunks_now) {
+              const float mn = fmaxf(m_e[k], ms[k][j]);
+              const float fa = exp2f(m_e[k] - mn), fb = exp2f(ms[k][j] - mn);
+              L_e[k] = L_e[k] * fa + ls[k][j] * fb;
+              o_e[k] = o_e[k] * fa + os[k][j] * fb;
+              m_e[k] = mn;
+            }
+          }
+        }
+      }
+    }
+#pragma unroll
+    for (int k = 0; k < NE; ++k) {
+      const int idx = tid + k * kThreads;
+      if (k < ne && idx < G * D) {
+        const int gg = idx / D, c = idx % D;
+        p.out[(orow0 + gg) * D + c] = o_e[k] / L_e[k];
+        if (c == 0) {
+          if (p.lse) p.lse[orow0 + gg] = (m_e[k] + log2f(L_e[k])) * 0.6931471805599453f;
+          if (p.track) {
+            p.mlprev[(orow0 + gg) * 2] = m_e[k];
+            p.mlprev[(orow0 + gg) * 2 + 1] = L_e[k];
+          }
+        }
       }
     }
   }
-  if (hq == 0 && c == 0) {
-    if (p.qprev) p.nprev[b] = n_now;
-    if (p.appended && n_now > 0) {
-      p.seq_len[b] = n_now;
-      p.next_pos[b] += 1;
-    }
-  }
+  DYNTS_STAMP(7);
+  seq_checkin();
 }
 
 }  // namespace dynts

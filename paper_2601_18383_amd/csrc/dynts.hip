@@ -2,9 +2,11 @@
 // kernel launches.  Nothing here allocates device memory or synchronises the host.
 #include "../../include/dynts.h"
 
+#include <hip/hip_ext.h>
 #include <hip/hip_runtime.h>
 
 #include <cmath>
+#include <cstdlib>
 #include <cstring>
 #include <new>
 #include <vector>
@@ -21,8 +23,8 @@ constexpr int kSelectLdsMax = 16384;  // candidates whose keys are cached in LDS
 size_t align_up(size_t v) { return (v + kAlign - 1) / kAlign * kAlign; }
 
 struct Plan {
-  int G = 0, chunk = 0, nsplit = 0;
-  size_t off_part_o = 0, off_part_ml = 0, off_ncur = 0, off_qprev = 0, off_mlprev = 0, off_nprev = 0;
+  int G = 0, waves = 0, chunk = 0, nsplit = 0;
+  size_t off_part_o = 0, off_part_ml = 0, off_unit_cnt = 0, off_seq_cnt = 0, off_qprev = 0, off_mlprev = 0, off_nprev = 0;
   size_t bytes = 0;
 };
 
@@ -41,25 +43,41 @@ int check_config(const dynts_config *c) {
   return DYNTS_OK;
 }
 
-// Split every (sequence, KV head) cache into chunks of whole 128-slot quanta so that the
-// grid has a few workgroups per compute unit without drowning in partials.
+// Split every (sequence, KV head) cache into chunks, one workgroup per chunk.  Workgroups have
+// 8 waves (one per compute unit fits) when that still fills the chip, else 4; chunks are whole
+// multiples of the workgroup's tile quantum.  The aim is about one 8-wave workgroup per compute
+// unit: few enough that every wave loops over many tiles with its loads in flight, and that
+// the split partials stay small.
 Plan make_plan(const dynts_config &c) {
   Plan p;
   p.G = c.n_q_heads / c.n_kv_heads;
   const long long units = (long long)c.batch * c.n_kv_heads;
-  const int quanta = (c.capacity + dynts::kChunkQuantum - 1) / dynts::kChunkQuantum;
-  const long long target = 256LL * 8;  // workgroups wanted in flight
-  int per = 1;                         // quanta per chunk
-  while (per < quanta && units * ((quanta + per) / (per + 1)) >= target) ++per;
-  p.chunk = per * dynts::kChunkQuantum;
+  long long target = 256;  // workgroups wanted (256 compute units)
+  p.waves = 8;
+  if (const char *e = std::getenv("DYNTS_TARGET_WGS")) {
+    long long v = std::atoll(e);
+    if (v > 0) target = v;
+  }
+  if (const char *e = std::getenv("DYNTS_WAVES")) {
+    int v = std::atoi(e);
+    if (v == 4 || v == 8) p.waves = v;
+  }
+  const int quantum = p.waves * dynts::kTile;
+  const int quanta = (c.capacity + quantum - 1) / quantum;
+  long long want = (target + units / 2) / units;
+  if (want < 1) want = 1;
+  if (want > quanta) want = quanta;
+  const int per = (int)((quanta + want - 1) / want);  // quanta per chunk
+  p.chunk = per * quantum;
   p.nsplit = (c.capacity + p.chunk - 1) / p.chunk;
   const size_t rows = (size_t)units * p.nsplit * p.G;
   size_t off = 0;
   p.off_part_o = off;  off = align_up(off + rows * c.head_dim * sizeof(float));
   p.off_part_ml = off; off = align_up(off + rows * 2 * sizeof(float));
-  p.off_ncur = off;    off = align_up(off + (size_t)c.batch * sizeof(int32_t));
+  p.off_unit_cnt = off; off = align_up(off + (size_t)units * sizeof(uint32_t));
+  p.off_seq_cnt = off; off = align_up(off + (size_t)c.batch * sizeof(uint32_t));
   const size_t LB = (size_t)c.n_layers * c.batch;
-  p.off_qprev = off;   off = align_up(off + LB * c.n_q_heads * c.head_dim * sizeof(uint16_t));
+  p.off_qprev = off;   off = align_up(off + 2 * LB * c.n_q_heads * c.head_dim * sizeof(uint16_t));  // two copies, used in turn
   p.off_mlprev = off;  off = align_up(off + LB * c.n_q_heads * 2 * sizeof(float));
   p.off_nprev = off;   off = align_up(off + LB * sizeof(int32_t));
   p.bytes = off;
@@ -78,7 +96,9 @@ struct dynts_ctx {
   int32_t *pos = nullptr, *seq_len = nullptr, *next_pos = nullptr, *n_prompt = nullptr, *status = nullptr;
   unsigned char *ws = nullptr;
   std::vector<unsigned char> pending;  // per layer: a score update is owed
+  std::vector<unsigned char> qslot;    // per layer: which copy of the saved query is current
   hipEvent_t ev_start = nullptr, ev_stop = nullptr;
+  unsigned long long *trace = nullptr;
 };
 
 namespace {
@@ -96,7 +116,7 @@ struct LayerView {
   uint16_t *K, *V;
   float *S;
   int32_t *pos, *seq_len, *next_pos;
-  uint16_t *qprev;
+  uint16_t *qprev, *qnext;
   float *mlprev;
   int32_t *nprev;
 };
@@ -113,27 +133,33 @@ LayerView layer_view(const dynts_ctx *ctx, int layer) {
   v.seq_len = ctx->seq_len + (size_t)layer * c.batch;
   v.next_pos = ctx->next_pos + (size_t)layer * c.batch;
   const size_t LBq = (size_t)layer * c.batch * c.n_q_heads;
-  v.qprev = reinterpret_cast<uint16_t *>(ctx->ws + ctx->plan.off_qprev) + LBq * c.head_dim;
+  uint16_t *qbuf = reinterpret_cast<uint16_t *>(ctx->ws + ctx->plan.off_qprev) + 2 * LBq * c.head_dim;
+  const size_t qsz = (size_t)c.batch * c.n_q_heads * c.head_dim;
+  v.qprev = qbuf + (ctx->qslot[layer] ? qsz : 0);
+  v.qnext = qbuf + (ctx->qslot[layer] ? 0 : qsz);
   v.mlprev = reinterpret_cast<float *>(ctx->ws + ctx->plan.off_mlprev) + LBq * 2;
   v.nprev = reinterpret_cast<int32_t *>(ctx->ws + ctx->plan.off_nprev) + (size_t)layer * c.batch;
   return v;
 }
 
-template <int D, bool ATTEND, bool PENDING, bool APPEND>
-void launch_partial(const dynts::AttendParams &p, dim3 grid, hipStream_t st) {
-  hipLaunchKernelGGL((dynts::attend_partial_kernel<D, ATTEND, PENDING, APPEND>), grid, dim3(dynts::kThreads), 0, st, p);
+// start/stop (may be null) are attached to the dispatch itself, so their timestamps are the
+// kernel's own begin and end
+template <int D, int W, bool ATTEND, bool PENDING, bool APPEND>
+void launch_partial(const dynts::AttendParams &p, dim3 grid, hipStream_t st, hipEvent_t start, hipEvent_t stop) {
+  hipExtLaunchKernelGGL((dynts::attend_kernel<D, W, ATTEND, PENDING, APPEND>), grid, dim3(W * 64), 0, st, start, stop,
+                        0, p);
 }
 
-template <int D>
-void launch_partial_d(const dynts::AttendParams &p, dim3 grid, hipStream_t st, bool attend, bool pending,
-                      bool append) {
-  if (!attend) return launch_partial<D, false, true, false>(p, grid, st);
+template <int D, int W>
+void launch_partial_d(const dynts::AttendParams &p, dim3 grid, hipStream_t st, hipEvent_t e0, hipEvent_t e1,
+                      bool attend, bool pending, bool append) {
+  if (!attend) return launch_partial<D, W, false, true, false>(p, grid, st, e0, e1);
   if (pending) {
-    if (append) return launch_partial<D, true, true, true>(p, grid, st);
-    return launch_partial<D, true, true, false>(p, grid, st);
+    if (append) return launch_partial<D, W, true, true, true>(p, grid, st, e0, e1);
+    return launch_partial<D, W, true, true, false>(p, grid, st, e0, e1);
   }
-  if (append) return launch_partial<D, true, false, true>(p, grid, st);
-  return launch_partial<D, true, false, false>(p, grid, st);
+  if (append) return launch_partial<D, W, true, false, true>(p, grid, st, e0, e1);
+  return launch_partial<D, W, true, false, false>(p, grid, st, e0, e1);
 }
 
 // attend (optionally with fused append) and/or the deferred score update of one layer
@@ -149,33 +175,29 @@ int run_attend(dynts_ctx *ctx, int layer, const uint16_t *q, const uint16_t *k_n
   p.K = lv.K; p.V = lv.V; p.S = lv.S; p.pos = lv.pos;
   p.seq_len = lv.seq_len; p.n_prompt = ctx->n_prompt; p.next_pos = lv.next_pos;
   p.q = q; p.k_new = k_new; p.v_new = v_new; p.s_new = s_new; p.active = active;
-  p.qprev = lv.qprev; p.mlprev = lv.mlprev; p.nprev = lv.nprev;
+  p.out = out; p.lse = lse;
+  p.qprev = lv.qprev; p.qnext = lv.qnext; p.mlprev = lv.mlprev; p.nprev = lv.nprev;
   p.part_o = reinterpret_cast<float *>(ctx->ws + pl.off_part_o);
   p.part_ml = reinterpret_cast<float *>(ctx->ws + pl.off_part_ml);
-  p.ncur = reinterpret_cast<int32_t *>(ctx->ws + pl.off_ncur);
+  p.unit_cnt = reinterpret_cast<uint32_t *>(ctx->ws + pl.off_unit_cnt);
+  p.seq_cnt = reinterpret_cast<uint32_t *>(ctx->ws + pl.off_seq_cnt);
   p.status = ctx->status;
   p.Nb = c.batch; p.Hq = c.n_q_heads; p.Hkv = c.n_kv_heads; p.G = pl.G; p.cap = c.capacity;
-  p.chunk = pl.chunk; p.nsplit = pl.nsplit; p.scale_log2 = ctx->scale_log2;
+  p.chunk = pl.chunk; p.nsplit = pl.nsplit; p.track = track ? 1 : 0; p.scale_log2 = ctx->scale_log2;
+  p.trace = ctx->trace;
 
   const dim3 grid(pl.nsplit, c.n_kv_heads, c.batch);
-  if (ctx->ev_start) (void)hipEventRecord(ctx->ev_start, st);
-  if (c.head_dim == 128) launch_partial_d<128>(p, grid, st, attend, apply_pending, append);
-  else launch_partial_d<64>(p, grid, st, attend, apply_pending, append);
-  if (ctx->ev_stop) (void)hipEventRecord(ctx->ev_stop, st);
-  int rc = launch_status();
-  if (rc != DYNTS_OK) return rc;
-  if (!attend) return DYNTS_OK;
-
-  dynts::MergeParams m;
-  m.part_o = p.part_o; m.part_ml = p.part_ml; m.ncur = p.ncur; m.q = q; m.out = out; m.lse = lse;
-  m.qprev = track ? lv.qprev : nullptr; m.mlprev = lv.mlprev; m.nprev = lv.nprev;
-  m.seq_len = lv.seq_len; m.next_pos = lv.next_pos;
-  m.Hq = c.n_q_heads; m.Hkv = c.n_kv_heads; m.G = pl.G; m.chunk = pl.chunk; m.nsplit = pl.nsplit;
-  m.appended = append ? 1 : 0;
-  const dim3 mgrid(c.n_q_heads, c.batch);
-  if (c.head_dim == 128) hipLaunchKernelGGL((dynts::attend_merge_kernel<128>), mgrid, dim3(128), 0, st, m);
-  else hipLaunchKernelGGL((dynts::attend_merge_kernel<64>), mgrid, dim3(64), 0, st, m);
-  return launch_status();
+  hipEvent_t e0 = ctx->ev_start, e1 = ctx->ev_stop;
+  if (c.head_dim == 128) {
+    if (pl.waves == 8) launch_partial_d<128, 8>(p, grid, st, e0, e1, attend, apply_pending, append);
+    else launch_partial_d<128, 4>(p, grid, st, e0, e1, attend, apply_pending, append);
+  } else {
+    if (pl.waves == 8) launch_partial_d<64, 8>(p, grid, st, e0, e1, attend, apply_pending, append);
+    else launch_partial_d<64, 4>(p, grid, st, e0, e1, attend, apply_pending, append);
+  }
+  const int rc = launch_status();
+  if (rc == DYNTS_OK && attend && track) ctx->qslot[layer] ^= 1;  // the query just saved becomes the current one
+  return rc;
 }
 
 }  // namespace
@@ -211,6 +233,7 @@ int dynts_create(const dynts_config *cfg, dynts_ctx **out) {
   const float scale = cfg->softmax_scale > 0.f ? cfg->softmax_scale : 1.0f / std::sqrt((float)cfg->head_dim);
   ctx->scale_log2 = scale * 1.4426950408889634f;
   ctx->pending.assign((size_t)cfg->n_layers, 0);
+  ctx->qslot.assign((size_t)cfg->n_layers, 0);
   *out = ctx;
   return DYNTS_OK;
 }
@@ -234,6 +257,7 @@ int dynts_bind(dynts_ctx *ctx, uint16_t *K, uint16_t *V, float *S, int32_t *pos,
   ctx->K = K; ctx->V = V; ctx->S = S; ctx->pos = pos; ctx->seq_len = seq_len; ctx->next_pos = next_pos;
   ctx->n_prompt = n_prompt; ctx->ws = static_cast<unsigned char *>(workspace); ctx->status = status;
   ctx->pending.assign(ctx->pending.size(), 0);
+  ctx->qslot.assign(ctx->qslot.size(), 0);
   ctx->bound = true;
   return DYNTS_OK;
 }
@@ -375,6 +399,15 @@ int dynts_set_kernel_events(dynts_ctx *ctx, void *start, void *stop) {
   ctx->ev_stop = static_cast<hipEvent_t>(stop);
   return DYNTS_OK;
 }
+
+#ifdef DYNTS_TRACE
+// Development builds only: 8 wall-clock stamps per workgroup of the next attend launches.
+int dynts_set_trace(dynts_ctx *ctx, unsigned long long *buf) {
+  if (!ctx) return DYNTS_ENULL;
+  ctx->trace = buf;
+  return DYNTS_OK;
+}
+#endif
 
 int dynts_decode_loop(dynts_ctx *ctx, int32_t n_steps, const uint16_t *q, const uint16_t *k_new,
                       const uint16_t *v_new, const float *s_new, const uint8_t *active, const uint8_t *evict_steps,
