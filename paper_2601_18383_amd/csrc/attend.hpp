@@ -133,7 +133,7 @@ __device__ __forceinline__ void wave_lds_fence() {
 
 template <int D, int W, bool ATTEND, bool PENDING, bool APPEND>
 __global__ __launch_bounds__(W * 64, 2) void attend_kernel(const AttendParams p) {
-  constexpr int kWaves = W, kThreads = W * 64, kChunkQuantum = W * kTile;
+  constexpr int kWaves = W, kThreads = W * 64;
   constexpr int KS = D / 32;              // MFMA k-steps per K row
   constexpr int CB = D / 16;              // 16-column blocks of the output
   constexpr int PIECES = D / 8;           // 16-byte pieces per row
@@ -162,8 +162,13 @@ __global__ __launch_bounds__(W * 64, 2) void attend_kernel(const AttendParams p)
   float *Sb = p.S + unit * (size_t)p.cap;
   unsigned char *vst = smem + wave * (kTile * VSTRIDE);
   const int vrow_l = lane / PIECES, vpiece = lane % PIECES;
-  const int r0 = split * p.chunk;
-  int t = r0 + kTile * wave;
+  // Work split of one (sequence, KV head) over its nsplit * W waves: wave wi first takes tile wi
+  // (a position known before the sequence length is, so its loads can leave at once); the slots
+  // past those first tiles are then cut into equal contiguous ranges, one per wave, from the
+  // actual length, so every wave moves the same number of bytes whatever the length.
+  const int NW = p.nsplit * kWaves;
+  const int wi = split * kWaves + wave;
+  int t = kTile * wi;
 
   // ---- request everything the prologue needs in one go -----------------------------------
   // Loads return in order, so the few scalars (lengths, activity) go first; right behind them
@@ -256,8 +261,11 @@ __global__ __launch_bounds__(W * 64, 2) void attend_kernel(const AttendParams p)
   const int n_vis = n_rows > n_prev ? n_rows : n_prev;
   // workgroups of this unit that produce an attention partial (chunk 0 always does when the
   // sequence is attended: it owns the appended token), and that have any work at all
-  const int chunks_now = n_now > 0 ? ((n_rows + p.chunk - 1) / p.chunk > 1 ? (n_rows + p.chunk - 1) / p.chunk : 1) : 0;
-  const int chunks_prev = (n_prev + p.chunk - 1) / p.chunk;
+  // (a workgroup has work iff its first wave's first tile starts inside the sequence)
+  constexpr int kFirst = kWaves * kTile;  // slots covered by a workgroup's first tiles
+  auto wgs_for = [&](int n) { int c = (n + kFirst - 1) / kFirst; return c < p.nsplit ? c : p.nsplit; };
+  const int chunks_now = n_now > 0 ? (wgs_for(n_rows) > 1 ? wgs_for(n_rows) : 1) : 0;
+  const int chunks_prev = wgs_for(n_prev);
   const int chunks_vis = chunks_now > chunks_prev ? chunks_now : chunks_prev;
 #pragma unroll
   for (int i = 0; i < 4; ++i)  // inv_l = 0 switches padded heads and idle sequences off
@@ -284,7 +292,11 @@ __global__ __launch_bounds__(W * 64, 2) void attend_kernel(const AttendParams p)
     seq_checkin();
     return;
   }
-  const int r1 = (r0 + p.chunk < n_vis) ? r0 + p.chunk : n_vis;
+  // this wave's contiguous range [ra, rb) behind the first tiles
+  const int base = kTile * NW;
+  const int per = n_vis > base ? (n_vis - base + NW - 1) / NW : 0;
+  const int ra = base + wi * per;
+  const int rb = ra + per < n_vis ? ra + per : n_vis;
 
   // keep this call's query for the next deferred score update (its own buffer: the old one is
   // still being read by the other workgroups of this launch)
@@ -327,19 +339,27 @@ __global__ __launch_bounds__(W * 64, 2) void attend_kernel(const AttendParams p)
     }
   }
 
-  // the first tile was fetched before the length was known: keep rows past it out of P.V
+  // the first tile was fetched before the length was known: keep rows past the sequence out of P.V
   if (ATTEND && t + kTile > n_rows) {
 #pragma unroll
     for (int it = 0; it < VIT; ++it) vf[it] = (t + VROWS * it + vrow_l < n_rows) ? vf[it] : u32x4{0u, 0u, 0u, 0u};
   }
-  const int k_last = n_vis > 0 ? n_vis : 1;   // row clamps of the prefetches (always a valid row)
-  const int v_last = n_rows > 0 ? n_rows : 1;
+  // Row clamps of the prefetches: a prefetch must not pull another wave's rows, so rows are
+  // clamped to the end of this wave's own range (or, with no range, of its first tile); the
+  // clamp row is always a valid row of the allocation.
+  const int own_end = ra < rb ? rb : (t + kTile < n_vis ? t + kTile : n_vis);
+  const int k_last = own_end > 0 ? own_end : 1;
+  const int v_end = own_end < n_rows ? own_end : n_rows;
+  const int v_last = v_end > 0 ? v_end : 1;
 
   // ---- one 32-slot tile of this wave -------------------------------------------------------
   // Branch-free apart from two wave-uniform guards; the next tile's loads are issued
   // unconditionally (clamped), so the loop never drains its outstanding loads.
-  auto tile = [&](int t) {
-    const int tn = t + kChunkQuantum;
+  // t: first slot of the tile; hi: end of the slots of this tile that belong to this wave;
+  // tn: first slot of the wave's next tile (any value when there is none: the loads are clamped)
+  auto tile = [&](int t, int hi, int tn) {
+    const int att_hi = hi < n_rows ? hi : n_rows;
+    const int pend_hi = hi < n_prev ? hi : n_prev;
 
     // logits for the current query (A = K rows, B = q) and for the previous one (swapped:
     // accp[s][i] = logit(slot t + 16 s + r16, head 4 kg + i))
@@ -362,7 +382,7 @@ __global__ __launch_bounds__(W * 64, 2) void attend_kernel(const AttendParams p)
     }
 
     // ---- deferred score update: S[slot] += sum over the group of alpha_prev[g][slot] --------
-    if (PENDING && t < n_prev) {
+    if (PENDING && t < pend_hi) {
       float part[2];
 #pragma unroll
       for (int s = 0; s < 2; ++s) {
@@ -378,18 +398,18 @@ __global__ __launch_bounds__(W * 64, 2) void attend_kernel(const AttendParams p)
         if (kg == 1) part[1] = other;
       }
       const int tok = t + lane;  // lane < 32: slot of sub-tile kg, row r16
-      if (lane < kTile && tok < n_prev && tok >= M) Sb[tok] = s_cur + (kg == 0 ? part[0] : part[1]);
+      if (lane < kTile && tok < pend_hi && tok >= M) Sb[tok] = s_cur + (kg == 0 ? part[0] : part[1]);
     }
 
     // ---- attention for the current query --------------------------------------------------
-    if (ATTEND && t < n_rows) {
+    if (ATTEND && t < att_hi) {
       // acc[s][i] = logit(slot t + 16 s + 4 kg + i, head g)
       float x[8];
       float mx = -INFINITY;
 #pragma unroll
       for (int e = 0; e < 8; ++e) {
         const int tok = t + 16 * (e >> 2) + 4 * kg + (e & 3);
-        x[e] = tok < n_rows ? acc[e >> 2][e & 3] * p.scale_log2 : -INFINITY;
+        x[e] = tok < att_hi ? acc[e >> 2][e & 3] * p.scale_log2 : -INFINITY;
         mx = fmaxf(mx, x[e]);
       }
       mx = fmaxf(mx, __shfl_xor(mx, 16));
@@ -440,7 +460,8 @@ __global__ __launch_bounds__(W * 64, 2) void attend_kernel(const AttendParams p)
   __builtin_amdgcn_s_waitcnt(0);  // development: when has everything the prologue asked for arrived
   DYNTS_STAMP(2);
 #endif
-  for (; t < r1; t += kChunkQuantum) tile(t);
+  if (t < n_vis) tile(t, t + kTile < n_vis ? t + kTile : n_vis, ra);
+  for (t = ra; t < rb; t += kTile) tile(t, rb, t + kTile);
   DYNTS_STAMP(3);
   DYNTS_STAMP(4);
 #ifdef DYNTS_TRACE_WAVES  // development: when each wave left its tile loop (overwrites the phase stamps)
