@@ -179,10 +179,12 @@ def run_gpu(args, wl):
     k_avg_ms = sum(k_ms) / len(k_ms)
     bytes_launch = sum(algorithmic_bytes(wl, [n] * wl.batch, wl.batch) for n in lens) / len(lens)
     achieved = bytes_launch / (k_avg_ms * 1e-3) / 1e9
-    traffic = None
-    tf = os.path.join(ROOT, "profiles", "attend_kernel_%s_traffic.json" % wl.name)
+    traffic = None  # HBM bytes per launch from the committed rocprofv3 counter summary, if there is one
+    tf = os.path.join(ROOT, "profiles", "attend_kernel_%s_hbm_counters.txt" % wl.name)
     if os.path.exists(tf):
-        traffic = json.load(open(tf)).get("hbm_bytes_per_launch")
+        for ln in open(tf):
+            if ln.startswith("hbm_bytes_per_launch:"):
+                traffic = int(ln.split(":")[1])
     roofline = {"bound": "hbm", "kernel": "attend_kernel<%d,attend,pending,append>" % wl.head_dim,
                 "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
                 "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": traffic,
@@ -195,7 +197,7 @@ def run_gpu(args, wl):
                 evictions_timed=int(ft.sum()), first_timed_step=t + args.warmup + 1)
 
 
-def run_cpu_baseline(wl, budget_s=20.0):
+def run_cpu_baseline(wl, budget_s=15.0):
     """The float64 oracle, as it stands, on the host cores: whole decode steps of the same
     workload from a generator-made steady state (one layer's worth scaled to all layers)."""
     import numpy as np
@@ -218,7 +220,7 @@ def run_cpu_baseline(wl, budget_s=20.0):
     o.next_pos[:] = o.pos[:, :, n0 - 1].max(axis=1) + 1
     o.steps_done[:] = wl.budget + wl.window + E  # a multiple of E: the next trigger is E steps away
     threads = orc.max_threads()
-    steps = torch.arange(10 ** 5, 10 ** 5 + 4 * E)
+    steps = torch.arange(10 ** 5, 10 ** 5 + max(4 * E, 1024))
     q = gen.q(0, steps).to(torch.float64).numpy()
     k, v = gen.kv(0, steps)
     k, v = k.to(torch.float64).numpy(), v.to(torch.float64).numpy()

@@ -194,7 +194,9 @@ class Synth:
             kc = (4.0 * self.mean_query(layer)).to(torch.bfloat16).view(1, 1, wl.n_kv_heads, wl.head_dim)
             K = torch.where(crit, kc, K)
         sc = hash_u64(stream_key(wl.seed, STREAM_SCORE, layer + 1), idx)
-        S = (_lsr(sc, 40).to(torch.float32) * (1.0 / (1 << 24))) ** 4 * 8.0  # heavy-ish tail in [0, 8)
+        x = _lsr(sc, 40).to(torch.float32) * (1.0 / (1 << 24))
+        x = x * x
+        S = x * x * 8.0  # heavy-ish tail in [0, 8); plain multiplications only, so CPU and GPU agree bit for bit
         S = torch.cat([torch.full((M, wl.batch, wl.n_kv_heads), float("inf"), device=dev), S], dim=0)
         out = dict(K=K.permute(1, 2, 0, 3).contiguous(), V=V.permute(1, 2, 0, 3).contiguous(),
                    S=S.permute(1, 2, 0).contiguous(), pos=pos.permute(1, 2, 0).to(torch.int32).contiguous())
