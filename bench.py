@@ -80,6 +80,16 @@ def make_pools(gen, wl, t0, n, device):
     return q, k, v, s
 
 
+def active_pool(lengths, t0, n, device):
+    """uint8 [n][Nb] on the device: is sequence b still decoding at steps t0+1 .. t0+n; None if all are."""
+    import torch
+    steps = torch.arange(t0 + 1, t0 + n + 1).view(-1, 1)
+    act = (steps <= lengths.view(1, -1))
+    if bool(act.all()):
+        return None, act
+    return act.to(torch.uint8).to(device).contiguous(), act
+
+
 def evict_flags(wl, t0, n):
     """Host flags of the trigger steps among t0+1 .. t0+n (every evict_every-th step once the
     thinking tokens exceed budget + window)."""
@@ -119,9 +129,7 @@ def run_gpu(args, wl):
     E = wl.evict_every
     t_steady = (wl.budget + wl.window + E) + 2 * E       # two periods past the first eviction
     t_steady = (t_steady + E - 1) // E * E
-    lo = wl.steps[0]
-    total = t_steady + args.warmup + args.steps
-    assert total <= lo, "timed window must end before the shortest sequence finishes (%d > %d)" % (total, lo)
+    lengths = gen.decode_lengths()  # per-sequence decode lengths (ragged workloads); finished ones are masked
     per_step = L * wl.batch * (wl.n_q_heads + 2 * wl.n_kv_heads) * wl.head_dim * 2
     block = max(E, min(256, (1 << 30) // per_step) // E * E)   # input pool of at most 1 GiB
     t = 0
@@ -129,8 +137,9 @@ def run_gpu(args, wl):
     while t < t_steady:
         n = min(block, t_steady - t)
         q, k, v, s = make_pools(gen, wl, t, n, dev)
-        B.dynts_decode_loop(cache.ctx, n, q, k, v, out, cache.keep_idx, cache.new_len, s_new=s,
-                            evict_steps=evict_flags(wl, t, n))
+        act, _ = active_pool(lengths, t, n, dev)
+        B.dynts_decode_loop(cache.ctx, n, q, k, v, out, cache.keep_idx, cache.new_len, s_new=s, active=act,
+                            evict_steps=evict_flags(wl, t, n), trigger=act)
         t += n
     torch.cuda.synchronize()
     log("steady state reached at step %d in %.1f s; seq_len[0,0]=%d status=%d" %
@@ -141,43 +150,44 @@ def run_gpu(args, wl):
     fw = evict_flags(wl, t, args.warmup)
     qt, kt, vt, stt = make_pools(gen, wl, t + args.warmup, args.steps, dev)
     ft = evict_flags(wl, t + args.warmup, args.steps)
+    aw, _ = active_pool(lengths, t, args.warmup, dev) if args.warmup else (None, None)
+    at, at_host = active_pool(lengths, t + args.warmup, args.steps, dev)
     torch.cuda.synchronize()
     if args.warmup:
         B.dynts_decode_loop(cache.ctx, args.warmup, qw, kw, vw, out, cache.keep_idx, cache.new_len, s_new=sw,
-                            evict_steps=fw)
+                            active=aw, evict_steps=fw, trigger=aw)
     torch.cuda.synchronize()
     t0 = time.perf_counter()
     B.dynts_decode_loop(cache.ctx, args.steps, qt, kt, vt, out, cache.keep_idx, cache.new_len, s_new=stt,
-                        evict_steps=ft)
+                        active=at, evict_steps=ft, trigger=at)
     torch.cuda.synchronize()
     dt = time.perf_counter() - t0
     t_end = t + args.warmup + args.steps
     assert int(cache.status[0]) == 0, "device status word set: %d" % int(cache.status[0])
-    assert int(cache.seq_len[0, 0]) == cache_len_before_step(wl, t_end + 1) - 1
+    longest = int(lengths.argmax())
+    assert int(cache.seq_len[0, longest]) == cache_len_before_step(wl, t_end + 1) - 1
 
     # ---- the streaming kernel alone, timed with HIP events recorded by the library ------------
     n_prof = min(args.steps, 64) // E * E or min(args.steps, 64)
     qp, kp, vp, sp = make_pools(gen, wl, t_end, n_prof, dev)
     fp = evict_flags(wl, t_end, n_prof)
+    # (the same native loop as the timed window, so the launches are back to back; every attend launch
+    # of the loop takes one event pair, in call order: step-major, layer-minor)
+    ap_dev, ap_host = active_pool(lengths, t_end, n_prof, dev)
     ev = HipEvents(n_prof * L)
-    stream = torch.cuda.current_stream().cuda_stream
-    lens = []
+    B.dynts_set_kernel_event_list(cache.ctx, [a for a, _ in ev.pairs], [b for _, b in ev.pairs])
+    B.dynts_decode_loop(cache.ctx, n_prof, qp, kp, vp, out, cache.keep_idx, cache.new_len, s_new=sp,
+                        active=ap_dev, evict_steps=fp, trigger=ap_dev)
+    B.dynts_set_kernel_event_list(cache.ctx, [], [])
+    launch_bytes = []
     for i in range(n_prof):
-        for l in range(L):
-            a, b = ev.pairs[i * L + l]
-            B.dynts_set_kernel_events(cache.ctx, a, b)
-            B.dynts_decode_step(cache.ctx, l, qp[i, l], kp[i, l], vp[i, l], out[l],
-                                s_new=sp[i] if sp is not None else None, stream=stream)
-            B.dynts_set_kernel_events(cache.ctx, None, None)
-            if fp[i]:
-                B.dynts_select_evict(cache.ctx, l, cache.keep_idx, cache.new_len, -1, stream=stream)
-                B.dynts_compact(cache.ctx, l, cache.keep_idx, cache.new_len, stream=stream)
-        lens.append(cache_len_before_step(wl, t_end + 1 + i))
+        n_act = int(ap_host[i].sum())
+        launch_bytes.append(algorithmic_bytes(wl, [cache_len_before_step(wl, t_end + 1 + i)] * n_act, n_act))
     torch.cuda.synchronize()
     k_ms = [ev.elapsed_ms(i) for i in range(n_prof * L)]
     ev.close()
     k_avg_ms = sum(k_ms) / len(k_ms)
-    bytes_launch = sum(algorithmic_bytes(wl, [n] * wl.batch, wl.batch) for n in lens) / len(lens)
+    bytes_launch = sum(launch_bytes) / len(launch_bytes)
     achieved = bytes_launch / (k_avg_ms * 1e-3) / 1e9
     traffic = None  # HBM bytes per launch from the committed rocprofv3 counter summary, if there is one
     tf = os.path.join(ROOT, "profiles", "attend_kernel_%s_hbm_counters.txt" % wl.name)
@@ -190,11 +200,13 @@ def run_gpu(args, wl):
                 "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": traffic,
                 "kernel_avg_us": round(k_avg_ms * 1e3, 2), "algorithmic_bytes_per_launch": int(bytes_launch),
                 "launches_timed": len(k_ms)}
-    step_bytes = sum(algorithmic_bytes(wl, [cache_len_before_step(wl, t + args.warmup + 1 + i)] * wl.batch,
-                                       wl.batch) for i in range(args.steps)) * L
+    act_counts = [int(at_host[i].sum()) for i in range(args.steps)]
+    step_bytes = sum(algorithmic_bytes(wl, [cache_len_before_step(wl, t + args.warmup + 1 + i)] * act_counts[i],
+                                       act_counts[i]) for i in range(args.steps)) * L
     return dict(value=args.steps / dt, ms_per_step=dt / args.steps * 1e3, roofline=roofline,
-                whole_step_gbs=step_bytes / dt / 1e9, seq_steps_per_s=args.steps * wl.batch / dt,
-                evictions_timed=int(ft.sum()), first_timed_step=t + args.warmup + 1)
+                whole_step_gbs=step_bytes / dt / 1e9, seq_steps_per_s=sum(act_counts) / dt,
+                evictions_timed=int(ft.sum()), first_timed_step=t + args.warmup + 1,
+                active_min=min(act_counts), active_max=max(act_counts))
 
 
 def run_cpu_baseline(wl, budget_s=15.0):
@@ -281,9 +293,9 @@ def main():
         "ms_per_step": round(r["ms_per_step"], 5), "higher_is_better": True, "scaling": "weak",
         "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
         "config": {"workload": "%s: %d layer(s), batch %d, %d q / %d kv heads, head_dim %d, prompt %d, budget %d, "
-                               "window %d, evict every %d; steady state, all sequences active" %
+                               "window %d, evict every %d; steady state, %d-%d of %d sequences active" %
                                (wl.name, wl.n_layers, wl.batch, wl.n_q_heads, wl.n_kv_heads, wl.head_dim, wl.prompt,
-                                wl.budget, wl.window, wl.evict_every),
+                                wl.budget, wl.window, wl.evict_every, r["active_min"], r["active_max"], wl.batch),
                    "first_timed_step": r["first_timed_step"], "evictions_in_window": r["evictions_timed"],
                    "sequence_steps_per_s": round(r["seq_steps_per_s"], 1),
                    "whole_step_algorithmic_GBps": round(r["whole_step_gbs"], 1)},

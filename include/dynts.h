@@ -169,6 +169,11 @@ int dynts_decode_loop(dynts_ctx *ctx, int32_t n_steps, const uint16_t *q, const 
  * hipEventElapsedTime(start, stop) is the kernel's own duration.  Pass NULLs to switch it off. */
 int dynts_set_kernel_events(dynts_ctx *ctx, void *start, void *stop);
 
+/* The same for a run of launches: `starts` and `stops` are host arrays of n hipEvent_t handles; the
+ * next n attend launches of this context (in call order, e.g. inside dynts_decode_loop) take one pair
+ * each, after which the hook is off again.  n = 0 clears the list. */
+int dynts_set_kernel_event_list(dynts_ctx *ctx, void *const *starts, void *const *stops, int32_t n);
+
 #ifdef __cplusplus
 }
 #endif

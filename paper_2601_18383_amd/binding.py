@@ -21,7 +21,7 @@ EXPORTS = [
     "dynts_version", "dynts_strerror", "dynts_create", "dynts_destroy", "dynts_workspace_bytes",
     "dynts_bind", "dynts_prefill", "dynts_append", "dynts_decode_attend", "dynts_update_scores",
     "dynts_decode_attend_update", "dynts_decode_step", "dynts_select_evict", "dynts_compact",
-    "dynts_decode_loop", "dynts_set_kernel_events",
+    "dynts_decode_loop", "dynts_set_kernel_events", "dynts_set_kernel_event_list",
 ]
 
 
@@ -57,6 +57,7 @@ def _load():
     lib.dynts_compact.argtypes = [vp, i32, vp, vp, i32, vp, vp]
     lib.dynts_decode_loop.argtypes = [vp, i32, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp, vp, vp]
     lib.dynts_set_kernel_events.argtypes = [vp, vp, vp]
+    lib.dynts_set_kernel_event_list.argtypes = [vp, C.POINTER(vp), C.POINTER(vp), i32]
     for name in EXPORTS:
         getattr(lib, name)
     return lib
@@ -190,6 +191,16 @@ def dynts_decode_loop(ctx, n_steps, q, k_new, v_new, out, keep_idx=None, new_len
 def dynts_set_kernel_events(ctx, start, stop):
     """start, stop: raw hipEvent_t handles (ints) or None."""
     _check(lib.dynts_set_kernel_events(ctx, start, stop), "dynts_set_kernel_events")
+
+
+def dynts_set_kernel_event_list(ctx, starts, stops):
+    """starts, stops: equally long lists of raw hipEvent_t handles (ctypes.c_void_p or ints)."""
+    n = len(starts)
+    assert len(stops) == n
+    arr = C.c_void_p * max(n, 1)
+    a = arr(*[s.value if isinstance(s, C.c_void_p) else s for s in starts]) if n else None
+    b = arr(*[s.value if isinstance(s, C.c_void_p) else s for s in stops]) if n else None
+    _check(lib.dynts_set_kernel_event_list(ctx, a, b, n), "dynts_set_kernel_event_list")
 
 
 class Cache:

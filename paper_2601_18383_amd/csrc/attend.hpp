@@ -125,6 +125,10 @@ __device__ __forceinline__ float coherent_load(const float *p) {
 }
 __device__ __forceinline__ void wait_own_stores() { __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup"); }
 
+// 2^x by the hardware instruction alone (v_exp_f32, ~1 ulp).  Arguments here are <= 0 up to
+// rounding; results below 2^-126 flush to zero, which is far under what the sums resolve.
+__device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
+
 __device__ __forceinline__ void wave_lds_fence() {
   __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
   __builtin_amdgcn_wave_barrier();
@@ -388,7 +392,7 @@ __global__ __launch_bounds__(W * 64, 2) void attend_kernel(const AttendParams p)
       for (int s = 0; s < 2; ++s) {
         float a = 0.f;
 #pragma unroll
-        for (int i = 0; i < 4; ++i) a += exp2f(accp[s][i] * p.scale_log2 - mprev[i]) * inv_lprev[i];
+        for (int i = 0; i < 4; ++i) a += fast_exp2(accp[s][i] * p.scale_log2 - mprev[i]) * inv_lprev[i];
         if (G > 4) a += __shfl_xor(a, 16);
         if (G > 8) a += __shfl_xor(a, 32);
         part[s] = a;
@@ -415,13 +419,13 @@ __global__ __launch_bounds__(W * 64, 2) void attend_kernel(const AttendParams p)
       mx = fmaxf(mx, __shfl_xor(mx, 16));
       mx = fmaxf(mx, __shfl_xor(mx, 32));
       const float m_new = fmaxf(m_run, mx);     // finite: the tile holds at least one valid slot
-      const float corr = exp2f(m_run - m_new);  // m_run = -inf on the first tile -> 0
+      const float corr = fast_exp2(m_run - m_new);  // m_run = -inf on the first tile -> 0
       m_run = m_new;
       bf16x8 ph, pl;
       float psum = 0.f;
 #pragma unroll
       for (int e = 0; e < 8; ++e) {
-        const float pe = exp2f(x[e] - m_new);
+        const float pe = fast_exp2(x[e] - m_new);
         psum += pe;
         const __bf16 hi = (__bf16)pe;
         ph[e] = hi;

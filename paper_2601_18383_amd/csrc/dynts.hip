@@ -98,6 +98,8 @@ struct dynts_ctx {
   std::vector<unsigned char> pending;  // per layer: a score update is owed
   std::vector<unsigned char> qslot;    // per layer: which copy of the saved query is current
   hipEvent_t ev_start = nullptr, ev_stop = nullptr;
+  std::vector<hipEvent_t> ev_list_start, ev_list_stop;  // one pair per coming attend launch
+  size_t ev_list_next = 0;
   unsigned long long *trace = nullptr;
 };
 
@@ -188,6 +190,11 @@ int run_attend(dynts_ctx *ctx, int layer, const uint16_t *q, const uint16_t *k_n
 
   const dim3 grid(pl.nsplit, c.n_kv_heads, c.batch);
   hipEvent_t e0 = ctx->ev_start, e1 = ctx->ev_stop;
+  if (attend && ctx->ev_list_next < ctx->ev_list_start.size()) {
+    e0 = ctx->ev_list_start[ctx->ev_list_next];
+    e1 = ctx->ev_list_stop[ctx->ev_list_next];
+    ++ctx->ev_list_next;
+  }
   if (c.head_dim == 128) {
     if (pl.waves == 8) launch_partial_d<128, 8>(p, grid, st, e0, e1, attend, apply_pending, append);
     else launch_partial_d<128, 4>(p, grid, st, e0, e1, attend, apply_pending, append);
@@ -408,6 +415,21 @@ int dynts_set_trace(dynts_ctx *ctx, unsigned long long *buf) {
   return DYNTS_OK;
 }
 #endif
+
+int dynts_set_kernel_event_list(dynts_ctx *ctx, void *const *starts, void *const *stops, int32_t n) {
+  if (!ctx) return DYNTS_ENULL;
+  if (n < 0) return DYNTS_EINVAL;
+  if (n > 0 && (!starts || !stops)) return DYNTS_ENULL;
+  ctx->ev_list_start.clear();
+  ctx->ev_list_stop.clear();
+  ctx->ev_list_next = 0;
+  for (int i = 0; i < n; ++i) {
+    if (!starts[i] || !stops[i]) return DYNTS_ENULL;
+    ctx->ev_list_start.push_back(static_cast<hipEvent_t>(starts[i]));
+    ctx->ev_list_stop.push_back(static_cast<hipEvent_t>(stops[i]));
+  }
+  return DYNTS_OK;
+}
 
 int dynts_decode_loop(dynts_ctx *ctx, int32_t n_steps, const uint16_t *q, const uint16_t *k_new,
                       const uint16_t *v_new, const float *s_new, const uint8_t *active, const uint8_t *evict_steps,
