@@ -86,30 +86,36 @@ __device__ __forceinline__ void store_bf16x8(uint16_t *p, bf16x8 v) {
   store_u32x4(p, __builtin_bit_cast(u32x4, v));
 }
 
-// K rows of the 32-slot tile at t as MFMA operand fragments; rows past n_vis repeat the last row
+// K rows of the 32-slot tile at t as MFMA operand fragments; rows past `end` repeat row end-1.
+// Addresses are a uniform base plus a 32-bit byte offset (a unit's cache is far below 4 GiB), which
+// keeps the per-tile address arithmetic to a clamp and a multiply-add per 16 rows.
 template <int D>
 __device__ __forceinline__ void load_k_tile(bf16x8 (&kf)[2][D / 32], const uint16_t *Kb, int t, int r16, int kg,
-                                            int n_vis) {
+                                            int end) {
+  const char *base = reinterpret_cast<const char *>(Kb);
 #pragma unroll
   for (int s = 0; s < 2; ++s) {
     int row = t + 16 * s + r16;
-    row = row < n_vis ? row : n_vis - 1;
-    const uint16_t *src = Kb + (size_t)row * D + 8 * kg;
+    row = row < end ? row : end - 1;
+    const uint32_t off = (uint32_t)row * (uint32_t)(2 * D) + 16u * (uint32_t)kg;
 #pragma unroll
-    for (int ks = 0; ks < D / 32; ++ks) kf[s][ks] = load_bf16x8(src + 32 * ks);
+    for (int ks = 0; ks < D / 32; ++ks)
+      kf[s][ks] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const u32x4 *>(base + off + 64 * ks));
   }
 }
 
-// V rows of the tile, whole rows across 16-byte pieces (coalesced); rows past n_now repeat the last row
+// V rows of the tile, whole rows across 16-byte pieces (coalesced); rows past `end` repeat row end-1
 template <int D>
 __device__ __forceinline__ void load_v_tile(u32x4 (&vf)[kTile / (64 / (D / 8))], const uint16_t *Vb, int t,
-                                            int lane, int n_now) {
+                                            int lane, int end) {
   constexpr int PIECES = D / 8, VROWS = 64 / PIECES;
+  const char *base = reinterpret_cast<const char *>(Vb);
+  const uint32_t lane_off = 16u * (uint32_t)(lane % PIECES);
 #pragma unroll
   for (int it = 0; it < kTile / VROWS; ++it) {
     int row = t + VROWS * it + lane / PIECES;
-    row = row < n_now ? row : n_now - 1;
-    vf[it] = load_u32x4(Vb + (size_t)row * D + 8 * (lane % PIECES));
+    row = row < end ? row : end - 1;
+    vf[it] = *reinterpret_cast<const u32x4 *>(base + ((uint32_t)row * (uint32_t)(2 * D) + lane_off));
   }
 }
 // Cross-workgroup traffic inside one launch (split partials, arrival counters) goes through
@@ -410,11 +416,19 @@ __global__ __launch_bounds__(W * 64, 2) void attend_kernel(const AttendParams p)
       // acc[s][i] = logit(slot t + 16 s + 4 kg + i, head g)
       float x[8];
       float mx = -INFINITY;
+      if (t + kTile <= att_hi) {  // wave-uniform: a full tile needs no masks
 #pragma unroll
-      for (int e = 0; e < 8; ++e) {
-        const int tok = t + 16 * (e >> 2) + 4 * kg + (e & 3);
-        x[e] = tok < att_hi ? acc[e >> 2][e & 3] * p.scale_log2 : -INFINITY;
-        mx = fmaxf(mx, x[e]);
+        for (int e = 0; e < 8; ++e) {
+          x[e] = acc[e >> 2][e & 3] * p.scale_log2;
+          mx = fmaxf(mx, x[e]);
+        }
+      } else {
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+          const int tok = t + 16 * (e >> 2) + 4 * kg + (e & 3);
+          x[e] = tok < att_hi ? acc[e >> 2][e & 3] * p.scale_log2 : -INFINITY;
+          mx = fmaxf(mx, x[e]);
+        }
       }
       mx = fmaxf(mx, __shfl_xor(mx, 16));
       mx = fmaxf(mx, __shfl_xor(mx, 32));
@@ -432,8 +446,10 @@ __global__ __launch_bounds__(W * 64, 2) void attend_kernel(const AttendParams p)
         pl[e] = (__bf16)(pe - (float)hi);
       }
       l_run = l_run * corr + psum;
+      {
 #pragma unroll
-      for (int cb = 0; cb < CB; ++cb) oacc[cb] *= corr;
+        for (int cb = 0; cb < CB; ++cb) oacc[cb] *= corr;
+      }
       // stage this tile's V rows in the wave's LDS tile, then fetch the next tile's
 #pragma unroll
       for (int it = 0; it < VIT; ++it)
