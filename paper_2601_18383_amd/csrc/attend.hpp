@@ -189,6 +189,7 @@ __global__ __launch_bounds__(W * 64, 2) void attend_kernel(const AttendParams p)
   const int len_raw = p.seq_len[b];
   const int prev_raw = PENDING ? p.nprev[b] : 0;
   const int M = p.n_prompt[b];
+  const int pos_new_all = APPEND ? p.next_pos[b] : 0;
   __builtin_amdgcn_sched_barrier(0);
   bf16x8 kf[2][KS];
   u32x4 vf[VIT];
@@ -241,7 +242,7 @@ __global__ __launch_bounds__(W * 64, 2) void attend_kernel(const AttendParams p)
     for (int ks = 0; ks < KS; ++ks) kn[ks] = load_bf16x8(knew + 32 * ks + 8 * kg);  // every operand row is k_new
 #pragma unroll
     for (int cb = 0; cb < CB; ++cb) vn[cb] = *reinterpret_cast<const uint2 *>(vnew + 16 * cb + 4 * kg);
-    pos_new = p.next_pos[b];
+    pos_new = pos_new_all;
     if (p.s_new) s_init = p.s_new[unit];
   }
 
@@ -281,25 +282,28 @@ __global__ __launch_bounds__(W * 64, 2) void attend_kernel(const AttendParams p)
   for (int i = 0; i < 4; ++i)  // inv_l = 0 switches padded heads and idle sequences off
     inv_lprev[i] = (PENDING && 4 * kg + i < G && n_prev > 0) ? 1.0f / inv_lprev[i] : 0.f;
 
-  // Every workgroup of the sequence checks in once it no longer needs seq_len / nprev; the
-  // last one advances them.  (A workgroup without work checks in right away.)
+  // Every workgroup of the sequence checks in as soon as its reads of seq_len / nprev / next_pos
+  // have come back (it works from registers afterwards); the last one to check in advances them.
+  // The check-in is issued early and its answer looked at later, so it costs no round trip at
+  // the end of the workgroup.
+  uint32_t seq_ticket = 0xffffffffu;
   auto seq_checkin = [&]() {
-    if (!ATTEND) return;
-    if (tid == 0) {
-      const uint32_t total = (uint32_t)p.nsplit * p.Hkv;
-      if (atomicAdd(&p.seq_cnt[b], 1u) == total - 1) {
-        __hip_atomic_store(&p.seq_cnt[b], 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        if (p.track) p.nprev[b] = n_now;
-        if (APPEND && appending) {
-          p.seq_len[b] = n_now;
-          p.next_pos[b] += 1;
-        }
+    if (ATTEND && tid == 0) seq_ticket = atomicAdd(&p.seq_cnt[b], 1u);
+  };
+  auto seq_settle = [&]() {
+    if (ATTEND && tid == 0 && seq_ticket == (uint32_t)p.nsplit * p.Hkv - 1) {
+      __hip_atomic_store(&p.seq_cnt[b], 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      if (p.track) p.nprev[b] = n_now;
+      if (APPEND && appending) {
+        p.seq_len[b] = n_now;
+        p.next_pos[b] = pos_new_all + 1;
       }
     }
   };
 
   if (split >= chunks_vis) {
     seq_checkin();
+    seq_settle();
     return;
   }
   // this wave's contiguous range [ra, rb) behind the first tiles
@@ -348,6 +352,8 @@ __global__ __launch_bounds__(W * 64, 2) void attend_kernel(const AttendParams p)
       p.pos[unit * (size_t)p.cap + n_old] = pos_new;
     }
   }
+
+  seq_checkin();
 
   // the first tile was fetched before the length was known: keep rows past the sequence out of P.V
   if (ATTEND && t + kTile > n_rows) {
@@ -481,6 +487,7 @@ __global__ __launch_bounds__(W * 64, 2) void attend_kernel(const AttendParams p)
   DYNTS_STAMP(2);
 #endif
   if (t < n_vis) tile(t, t + kTile < n_vis ? t + kTile : n_vis, ra);
+  seq_settle();
   for (t = ra; t < rb; t += kTile) tile(t, rb, t + kTile);
   DYNTS_STAMP(3);
   DYNTS_STAMP(4);
@@ -493,10 +500,7 @@ __global__ __launch_bounds__(W * 64, 2) void attend_kernel(const AttendParams p)
 
   if (!ATTEND) return;
   const bool has_partial = split < chunks_now;  // workgroup-uniform; false: the chunk only carried a deferred update
-  if (chunks_vis == 1 && !has_partial) {
-    seq_checkin();
-    return;
-  }
+  if (chunks_vis == 1 && !has_partial) return;
 
   // ---- combine the four waves ------------------------------------------------------------
   float *ored = reinterpret_cast<float *>(smem);
@@ -553,7 +557,6 @@ __global__ __launch_bounds__(W * 64, 2) void attend_kernel(const AttendParams p)
       }
     }
     DYNTS_STAMP(7);
-    seq_checkin();
     return;
   }
 
@@ -644,7 +647,6 @@ __global__ __launch_bounds__(W * 64, 2) void attend_kernel(const AttendParams p)
     }
   }
   DYNTS_STAMP(7);
-  seq_checkin();
 }
 
 }  // namespace dynts
