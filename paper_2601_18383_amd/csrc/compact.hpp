@@ -29,11 +29,16 @@ struct CompactParams {
 
 __device__ __forceinline__ int clamp_slot(int v, int cap) { return v < 0 ? 0 : (v >= cap ? cap - 1 : v); }
 
-// grid (3, Hkv, Nb): x = 0 moves K rows, 1 moves V rows, 2 moves S and pos.
+// grid (2 * kSlices + 1, Hkv, Nb): x < kSlices moves one 64-byte column slice of the K rows,
+// the next kSlices the same for V, the last one moves S and pos.  Column slices are independent
+// copies, so the in-place argument above holds for each of them; splitting a row over several
+// workgroups shortens the chain of dependent round trips (index, row, barrier, store) that bounds
+// this kernel: a trigger usually moves a few hundred rows per unit.
 template <int D>
 __global__ __launch_bounds__(kCompactThreads) void compact_kernel(const CompactParams p) {
-  constexpr int LPR = D / 8;                        // lanes per row (16 bytes each)
-  constexpr int ROWS = kCompactThreads / LPR;       // rows per pass
+  constexpr int kSlices = D * 2 / 64;               // 64-byte slices per row
+  constexpr int LPS = 4;                            // lanes per row slice (16 bytes each)
+  constexpr int ROWS = kCompactThreads / LPS;       // rows per pass
   constexpr int TILE = ROWS * kCompactUnroll;       // destinations per barrier
   __shared__ int sh_first;
   const int tid = threadIdx.x;
@@ -57,23 +62,26 @@ __global__ __launch_bounds__(kCompactThreads) void compact_kernel(const CompactP
   __syncthreads();
   const int first = sh_first;
 
-  if (what < 2) {
-    uint16_t *base = (what == 0 ? p.K : p.V) + unit * (size_t)p.cap * D;
-    const int r = tid / LPR, piece = tid % LPR;
+  if (what < 2 * kSlices) {
+    uint16_t *base = (what < kSlices ? p.K : p.V) + unit * (size_t)p.cap * D + 32 * (what % kSlices);
+    const int r = tid / LPS, piece = tid % LPS;
     for (int i0 = first; i0 < m; i0 += TILE) {
       uint4 buf[kCompactUnroll];
+      int src[kCompactUnroll];
 #pragma unroll
       for (int u = 0; u < kCompactUnroll; ++u) {
-        int i = i0 + u * ROWS + r;
-        if (i < m) {
-          int src = clamp_slot(ku[i], p.cap);
-          buf[u] = *reinterpret_cast<const uint4 *>(base + (size_t)src * D + 8 * piece);
-        }
+        const int i = i0 + u * ROWS + r;
+        src[u] = i < m ? clamp_slot(ku[i], p.cap) : 0;
+      }
+#pragma unroll
+      for (int u = 0; u < kCompactUnroll; ++u) {
+        const int i = i0 + u * ROWS + r;
+        if (i < m) buf[u] = *reinterpret_cast<const uint4 *>(base + (size_t)src[u] * D + 8 * piece);
       }
       __syncthreads();
 #pragma unroll
       for (int u = 0; u < kCompactUnroll; ++u) {
-        int i = i0 + u * ROWS + r;
+        const int i = i0 + u * ROWS + r;
         if (i < m) *reinterpret_cast<uint4 *>(base + (size_t)i * D + 8 * piece) = buf[u];
       }
     }
