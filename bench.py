@@ -27,10 +27,12 @@ def log(*a):
 
 
 def algorithmic_bytes(wl, n_list, n_active):
-    """Bytes one layer-step must move (K+V rows read, scores read+written, q in, out written,
-    the appended K/V row written), for cache lengths n_list of the active sequences."""
+    """Bytes one layer-step must move (K+V rows read, scores read+written unless they come from
+    outside, q in, out written, the appended K/V row written), for cache lengths n_list of the
+    active sequences."""
     d, Hkv, Hq, M = wl.head_dim, wl.n_kv_heads, wl.n_q_heads, wl.prompt
-    kv = sum(Hkv * (n * d * 2 * 2 + (n - M) * 8) for n in n_list)
+    s_bytes = 0 if wl.external_scores else 8
+    kv = sum(Hkv * (n * d * 2 * 2 + (n - M) * s_bytes) for n in n_list)
     return kv + n_active * Hq * d * (2 + 4) + 2 * n_active * Hkv * d * 2
 
 
@@ -90,23 +92,26 @@ def active_pool(lengths, t0, n, device):
     return act.to(torch.uint8).to(device).contiguous(), act
 
 
+def n_triggers_through(wl, t):
+    """Triggers among decode steps 1..t: the first when the thinking tokens fill budget + window +
+    evict_every slots, then one every evict_every steps (Sec. 5, the count of eviction events)."""
+    full = wl.budget + wl.window + wl.evict_every
+    return 0 if t < full else (t - full) // wl.evict_every + 1
+
+
 def evict_flags(wl, t0, n):
-    """Host flags of the trigger steps among t0+1 .. t0+n (every evict_every-th step once the
-    thinking tokens exceed budget + window)."""
+    """Host flags of the trigger steps among t0+1 .. t0+n."""
     import torch
     f = torch.zeros(n, dtype=torch.uint8)
     for i in range(n):
         t = t0 + 1 + i
-        if t % wl.evict_every == 0 and t > wl.budget + wl.window:
-            f[i] = 1
+        f[i] = n_triggers_through(wl, t) - n_triggers_through(wl, t - 1)
     return f
 
 
 def cache_len_before_step(wl, t):
     """Slots attended at decode step t (after the append, before any eviction of that step)."""
-    E, BW = wl.evict_every, wl.budget + wl.window
-    ev = max(0, (t - 1 - BW) // E) if t - 1 > BW else 0
-    return wl.prompt + t - ev * E
+    return wl.prompt + t - n_triggers_through(wl, t - 1) * wl.evict_every
 
 
 def run_gpu(args, wl):
@@ -127,11 +132,10 @@ def run_gpu(args, wl):
 
     # ---- bring the cache to steady state through the path itself (untimed) -----------------
     E = wl.evict_every
-    t_steady = (wl.budget + wl.window + E) + 2 * E       # two periods past the first eviction
-    t_steady = (t_steady + E - 1) // E * E
+    t_steady = (wl.budget + wl.window + E) + 2 * E       # the step of the third trigger
     lengths = gen.decode_lengths()  # per-sequence decode lengths (ragged workloads); finished ones are masked
     per_step = L * wl.batch * (wl.n_q_heads + 2 * wl.n_kv_heads) * wl.head_dim * 2
-    block = max(E, min(256, (1 << 30) // per_step) // E * E)   # input pool of at most 1 GiB
+    block = max(1, min(256, (1 << 30) // per_step))   # input pool of at most 1 GiB
     t = 0
     t_pre = time.perf_counter()
     while t < t_steady:
@@ -209,6 +213,59 @@ def run_gpu(args, wl):
                 active_min=min(act_counts), active_max=max(act_counts))
 
 
+def run_trajectory(args, wl):
+    """The whole decode of the workload, from the prompt to the end of the longest sequence, through
+    the native loop; finished sequences of a ragged batch are masked out.  Inputs are generated block
+    by block (untimed); only the loops are timed, one host synchronisation per block."""
+    import torch
+    from paper_2601_18383_amd import binding as B, synth
+
+    dev = torch.device("cuda:0")
+    gen = synth.Synth(wl, dev)
+    cache = B.Cache.for_workload(wl, device=dev)
+    L = wl.n_layers
+    for l in range(L):
+        K0, V0 = gen.prompt_kv(l)
+        m = torch.full((wl.batch,), wl.prompt, dtype=torch.int32, device=dev)
+        B.dynts_prefill(cache.ctx, l, K0, V0, m)
+    out = torch.zeros((L, wl.batch, wl.n_q_heads, wl.head_dim), dtype=torch.float32, device=dev)
+    lengths = gen.decode_lengths()
+    t_max = int(lengths.max()) if not args.max_steps else min(int(lengths.max()), args.max_steps)
+    per_step = L * wl.batch * (wl.n_q_heads + 2 * wl.n_kv_heads) * wl.head_dim * 2
+    block = max(1, min(256, (1 << 30) // per_step))
+    t, busy, seq_steps, alg_bytes, n_evict, t_log = 0, 0.0, 0, 0, 0, time.perf_counter()
+    while t < t_max:
+        n = min(block, t_max - t)
+        q, k, v, s = make_pools(gen, wl, t, n, dev)
+        act, act_host = active_pool(lengths, t, n, dev)
+        flags = evict_flags(wl, t, n)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        B.dynts_decode_loop(cache.ctx, n, q, k, v, out, cache.keep_idx, cache.new_len, s_new=s, active=act,
+                            evict_steps=flags, trigger=act)
+        torch.cuda.synchronize()
+        busy += time.perf_counter() - t0
+        for i in range(n):
+            na = int(act_host[i].sum())
+            seq_steps += na
+            alg_bytes += L * algorithmic_bytes(wl, [cache_len_before_step(wl, t + 1 + i)] * na, na)
+        n_evict += int(flags.sum())
+        t += n
+        if time.perf_counter() - t_log > 20:
+            t_log = time.perf_counter()
+            log("  step %d of %d, %.1f s in the loops so far" % (t, t_max, busy))
+    assert int(cache.status[0]) == 0, "device status word set: %d" % int(cache.status[0])
+    longest = int(lengths.argmax())
+    if t_max == int(lengths.max()):
+        assert int(cache.seq_len[0, longest]) == cache_len_before_step(wl, t_max + 1) - 1
+    roofline = {"bound": "hbm", "kernel": "whole run, all kernels", "achieved": round(alg_bytes / busy / 1e9, 1),
+                "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": round(alg_bytes / busy / 1e9 / HBM_PEAK_GBS, 4),
+                "traffic": None}
+    return dict(value=t_max / busy, ms_per_step=busy / t_max * 1e3, roofline=roofline,
+                whole_step_gbs=alg_bytes / busy / 1e9, seq_steps_per_s=seq_steps / busy, evictions_timed=n_evict,
+                first_timed_step=1, active_min=int(act_host[-1].sum()), active_max=wl.batch, steps=t_max)
+
+
 def run_cpu_baseline(wl, budget_s=15.0):
     """The float64 oracle, as it stands, on the host cores: whole decode steps of the same
     workload from a generator-made steady state (one layer's worth scaled to all layers)."""
@@ -264,6 +321,13 @@ def main():
     ap.add_argument("--layers", type=int, default=0, help="run only this many layers of the workload's stack "
                     "(a tuning aid; the workload line says so)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--trajectory", action="store_true",
+                    help="time the whole decode from the prompt to the end of the longest sequence (ragged "
+                         "batches decay) instead of a steady-state window; --steps/--warmup are ignored")
+    ap.add_argument("--max-steps", type=int, default=0, help="with --trajectory: stop after this many steps")
+    ap.add_argument("--full-kv", action="store_true",
+                    help="the comparison run without eviction: same inputs, a cache that holds every token, "
+                         "attention only (no score is kept)")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run three plain 1 GiB device copies (a kernel of known traffic, for scaling "
                          "rocprofv3's FETCH_SIZE / WRITE_SIZE counters)")
@@ -277,8 +341,18 @@ def main():
         import dataclasses
         wl = dataclasses.replace(wl, name="%s[%d of %d layers]" % (wl.name, args.layers, wl.n_layers),
                                  n_layers=args.layers)
+    if args.full_kv:
+        import dataclasses
+        hi = wl.steps[1] if not args.max_steps else min(wl.steps[1], args.max_steps)
+        wl = dataclasses.replace(wl, name=wl.name + " full-KV (no eviction, no scores)", budget=hi, window=0,
+                                 evict_every=1, external_scores=True)
+        args.trajectory = True
     log("host cores: %d; workload %s" % (os.cpu_count(), wl))
-    r = run_gpu(args, wl)
+    if args.trajectory:
+        r = run_trajectory(args, wl)
+        args.steps, args.warmup, args.no_cpu_baseline = r["steps"], 0, True
+    else:
+        r = run_gpu(args, wl)
     if args.copy_calibration:
         import torch
         src = torch.ones(1 << 28, dtype=torch.float32, device="cuda:0")
@@ -293,7 +367,8 @@ def main():
         "ms_per_step": round(r["ms_per_step"], 5), "higher_is_better": True, "scaling": "weak",
         "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
         "config": {"workload": "%s: %d layer(s), batch %d, %d q / %d kv heads, head_dim %d, prompt %d, budget %d, "
-                               "window %d, evict every %d; steady state, %d-%d of %d sequences active" %
+                               "window %d, evict every %d; " + ("whole decode from the prompt" if args.trajectory else "steady state") +
+                               ", %d-%d of %d sequences active" %
                                (wl.name, wl.n_layers, wl.batch, wl.n_q_heads, wl.n_kv_heads, wl.head_dim, wl.prompt,
                                 wl.budget, wl.window, wl.evict_every, r["active_min"], r["active_max"], wl.batch),
                    "first_timed_step": r["first_timed_step"], "evictions_in_window": r["evictions_timed"],

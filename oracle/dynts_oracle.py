@@ -133,8 +133,9 @@ class OracleLayer:
 
     budget/window/evict_every follow the benchmark's reading of Sec. 4.2: after a
     trigger the selection window holds `budget` slots and the local window
-    `window` slots; a trigger falls on every `evict_every`-th step of a sequence
-    once its thinking tokens exceed budget+window.  In the paper's notation the
+    `window` slots; a trigger falls on the step at which a sequence's thinking
+    tokens reach budget+window+evict_every, i.e. every `evict_every`-th step from
+    then on.  In the paper's notation the
     total budget is B = M + budget + window + evict_every and the eviction volume
     is K = evict_every.
     """
@@ -178,9 +179,10 @@ class OracleLayer:
             update_scores(self.S, alpha, self.seq_len, self.n_prompt, active)
 
     def due(self, active=None):
-        """Trigger mask after a step: every evict_every-th own step, once over budget+window."""
+        """Trigger mask after a step: the cache has reached its total budget (Sec. 4.2).  Sec. 5 counts
+        the same events: the first when M + i reaches B, then one every K steps."""
         n_think = self.seq_len - self.n_prompt
-        trig = (self.steps_done % self.evict_every == 0) & (n_think > self.budget + self.window)
+        trig = n_think >= self.budget + self.window + self.evict_every
         if active is not None:
             trig &= active.astype(bool)
         return trig.astype(_u8)

@@ -1,4 +1,4 @@
-"""The five benchmark workloads as named presets (shapes only; all tensors are synthetic).
+"""The benchmark workloads as named presets (shapes only; all tensors are synthetic).
 
 Shapes follow the attention geometry of the two 7-8B reasoning models the paper
 evaluates (Sec. 6.1): 32 query / 8 KV heads (Llama-3-8B-shaped) and 28 query /
@@ -63,6 +63,28 @@ CONFIGS = {
 # Same streams as cfg5, scores supplied from outside on a 64-level grid so that
 # every trigger has exact ties at the cut.
 CONFIGS["cfg5b"] = replace(CONFIGS["cfg5"], name="cfg5b", external_scores=True)
+
+
+
+
+def paper_schedule(name, n_q_heads, n_kv_heads, total, window, retention, batch=32, prompt=256,
+                   steps=16384, seed=0xD7A50010) -> Workload:
+    """A workload with the budget settings of the paper's own runs (Sec. 6.1, inference settings):
+    `total` thinking tokens fill the cache, the newest `window` of them are the local window, and a
+    trigger keeps the fraction `retention` of the others.  One trigger therefore evicts
+    (1 - retention) * (total - window) tokens at once, and the next one comes that many steps later
+    (e.g. 3000 / 1500 / 0.4 evicts 900, the eviction volume the paper quotes in Sec. 6.3)."""
+    keep = int(round(retention * (total - window)))
+    return Workload(name, 1, batch, n_q_heads, n_kv_heads, 128, prompt, (steps, steps), keep, window,
+                    total - window - keep, (0.02, 0.02), seed=seed)
+
+
+# The paper's budget settings on the two model shapes: hard benchmarks 5000 / 2000, simpler ones
+# 3000 / 1500 (R1-Qwen-shaped, retention 0.4) and 3000 / 1000 (R1-Llama-shaped, retention 0.3).
+CONFIGS["paper_qwen_5000"] = paper_schedule("paper_qwen_5000", 28, 4, 5000, 2000, 0.4, seed=0xD7A50011)
+CONFIGS["paper_qwen_3000"] = paper_schedule("paper_qwen_3000", 28, 4, 3000, 1500, 0.4, seed=0xD7A50012)
+CONFIGS["paper_llama_5000"] = paper_schedule("paper_llama_5000", 32, 8, 5000, 2000, 0.3, seed=0xD7A50013)
+CONFIGS["paper_llama_3000"] = paper_schedule("paper_llama_3000", 32, 8, 3000, 1000, 0.3, seed=0xD7A50014)
 
 
 def get(name: str) -> Workload:

@@ -29,8 +29,8 @@ struct CompactParams {
 
 __device__ __forceinline__ int clamp_slot(int v, int cap) { return v < 0 ? 0 : (v >= cap ? cap - 1 : v); }
 
-// grid (2 * kSlices + 1, Hkv, Nb): x < kSlices moves one 64-byte column slice of the K rows,
-// the next kSlices the same for V, the last one moves S and pos.  Column slices are independent
+// grid (2 * kSlices + 2, Hkv, Nb): x < kSlices moves one 64-byte column slice of the K rows,
+// the next kSlices the same for V, the last two move S and pos.  Column slices are independent
 // copies, so the in-place argument above holds for each of them; splitting a row over several
 // workgroups shortens the chain of dependent round trips (index, row, barrier, store) that bounds
 // this kernel: a trigger usually moves a few hundred rows per unit.
@@ -65,45 +65,65 @@ __global__ __launch_bounds__(kCompactThreads) void compact_kernel(const CompactP
   if (what < 2 * kSlices) {
     uint16_t *base = (what < kSlices ? p.K : p.V) + unit * (size_t)p.cap * D + 32 * (what % kSlices);
     const int r = tid / LPS, piece = tid % LPS;
+    // Two tiles in flight: the rows of tile t+1 are requested before tile t is stored.  That is safe
+    // because every source of tile t+1 lies at or beyond its own first destination, past all of
+    // tile t's destinations; the barrier still separates tile t's loads from tile t's stores.
+    typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+    u32x4 cur[kCompactUnroll], nxt[kCompactUnroll];
+    int src[kCompactUnroll];
+    // (rows past the end read slot 0 and are never stored, so every load is unconditional)
+#define DYNTS_COMPACT_IDX(i0_)                                   \
+  _Pragma("unroll") for (int u = 0; u < kCompactUnroll; ++u) {   \
+    const int i = (i0_) + u * ROWS + r;                          \
+    src[u] = i < m ? clamp_slot(ku[i], p.cap) : 0;               \
+  }
+#define DYNTS_COMPACT_ROWS(buf_)                                 \
+  _Pragma("unroll") for (int u = 0; u < kCompactUnroll; ++u)     \
+      buf_[u] = *reinterpret_cast<const u32x4 *>(base + (size_t)src[u] * D + 8 * piece);
+    DYNTS_COMPACT_IDX(first)
+    DYNTS_COMPACT_ROWS(cur)
+    DYNTS_COMPACT_IDX(first + TILE)
     for (int i0 = first; i0 < m; i0 += TILE) {
-      uint4 buf[kCompactUnroll];
-      int src[kCompactUnroll];
+      DYNTS_COMPACT_ROWS(nxt)
+      DYNTS_COMPACT_IDX(i0 + 2 * TILE)
+      __syncthreads();
 #pragma unroll
       for (int u = 0; u < kCompactUnroll; ++u) {
         const int i = i0 + u * ROWS + r;
+        if (i < m) *reinterpret_cast<u32x4 *>(base + (size_t)i * D + 8 * piece) = cur[u];
+      }
+#pragma unroll
+      for (int u = 0; u < kCompactUnroll; ++u) cur[u] = nxt[u];
+    }
+#undef DYNTS_COMPACT_IDX
+#undef DYNTS_COMPACT_ROWS
+  } else {
+    // S (x == 2 * kSlices) or pos (the last x): 4-byte elements, kScalarUnroll per thread and pass
+    constexpr int kScalarUnroll = 8;
+    constexpr int STILE = kCompactThreads * kScalarUnroll;
+    uint32_t *eu = (what == 2 * kSlices ? reinterpret_cast<uint32_t *>(p.S) : reinterpret_cast<uint32_t *>(p.pos)) +
+                   unit * (size_t)p.cap;
+    for (int i0 = first; i0 < m; i0 += STILE) {
+      int src[kScalarUnroll];
+      uint32_t val[kScalarUnroll];
+#pragma unroll
+      for (int u = 0; u < kScalarUnroll; ++u) {
+        const int i = i0 + u * kCompactThreads + tid;
         src[u] = i < m ? clamp_slot(ku[i], p.cap) : 0;
       }
 #pragma unroll
-      for (int u = 0; u < kCompactUnroll; ++u) {
-        const int i = i0 + u * ROWS + r;
-        if (i < m) buf[u] = *reinterpret_cast<const uint4 *>(base + (size_t)src[u] * D + 8 * piece);
+      for (int u = 0; u < kScalarUnroll; ++u) {
+        const int i = i0 + u * kCompactThreads + tid;
+        if (i < m) val[u] = eu[src[u]];
       }
       __syncthreads();
 #pragma unroll
-      for (int u = 0; u < kCompactUnroll; ++u) {
-        const int i = i0 + u * ROWS + r;
-        if (i < m) *reinterpret_cast<uint4 *>(base + (size_t)i * D + 8 * piece) = buf[u];
+      for (int u = 0; u < kScalarUnroll; ++u) {
+        const int i = i0 + u * kCompactThreads + tid;
+        if (i < m) eu[i] = val[u];
       }
     }
-  } else {
-    float *Su = p.S + unit * (size_t)p.cap;
-    int32_t *pu = p.pos + unit * (size_t)p.cap;
-    for (int i0 = first; i0 < m; i0 += kCompactThreads) {
-      int i = i0 + tid;
-      float s = 0.f;
-      int32_t q = 0;
-      if (i < m) {
-        int src = clamp_slot(ku[i], p.cap);
-        s = Su[src];
-        q = pu[src];
-      }
-      __syncthreads();
-      if (i < m) {
-        Su[i] = s;
-        pu[i] = q;
-      }
-    }
-    if (h == 0 && tid == 0) p.seq_len[b] = m;
+    if (what == 2 * kSlices && h == 0 && tid == 0) p.seq_len[b] = m;
   }
 }
 

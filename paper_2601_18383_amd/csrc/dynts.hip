@@ -392,7 +392,7 @@ int dynts_compact(dynts_ctx *ctx, int32_t layer, const uint8_t *trigger, const i
   const LayerView lv = layer_view(ctx, layer);
   dynts::CompactParams p{lv.K, lv.V, lv.S, lv.pos, lv.seq_len, trigger, keep_idx, new_len,
                          c.n_kv_heads, c.capacity, keep_stride};
-  const dim3 grid(2 * (c.head_dim * 2 / 64) + 1, c.n_kv_heads, c.batch);
+  const dim3 grid(2 * (c.head_dim * 2 / 64) + 2, c.n_kv_heads, c.batch);
   hipStream_t st = static_cast<hipStream_t>(stream);
   if (c.head_dim == 128) hipLaunchKernelGGL((dynts::compact_kernel<128>), grid, dim3(dynts::kCompactThreads), 0, st, p);
   else hipLaunchKernelGGL((dynts::compact_kernel<64>), grid, dim3(dynts::kCompactThreads), 0, st, p);

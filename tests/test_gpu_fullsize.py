@@ -139,6 +139,15 @@ def test_cfg5b_external_scores_with_ties(B):
     _run(B, "cfg5b", [3], [1, 126], n_steps=2, n0_delta=14)
 
 
+def test_paper_budget_settings_full_shape(B):
+    """The paper's budget settings (Sec. 6.1): a full cache of 5000 (3000) thinking tokens, one trigger that
+    keeps 0.4 (0.3) of the selection window and moves every row behind the first evicted one."""
+    wl = configs.get("paper_qwen_5000")
+    _run(B, "paper_qwen_5000", [0], [0, 31], n_steps=2, n0_delta=wl.evict_every - 2)
+    wl = configs.get("paper_llama_3000")
+    _run(B, "paper_llama_3000", [0], [7], n_steps=2, n0_delta=wl.evict_every - 2)
+
+
 def test_ragged_batch_full_shape(B):
     """cfg3 shape with per-sequence lengths and a mask of finished sequences, through the native loop."""
     wl = configs.get("cfg3")

@@ -53,6 +53,30 @@ def test_trajectory_small(B, mode, d, Hq, Hkv):
     assert int(sbs.c.seq_len[0, 1].item()) == sbs.o.seq_len[1]
 
 
+@pytest.mark.parametrize("mode", ["fused", "step"])
+def test_trajectory_paper_shaped_schedule(B, mode):
+    """The paper's own budget shape (Sec. 6.1, inference settings) in small: a wide local window, and a
+    trigger that keeps 0.4 of the other tokens, so one trigger evicts many rows at once and
+    budget + window is not a multiple of the period."""
+    rng = np.random.default_rng(4242)
+    Nb, Hq, Hkv, d = 2, 28, 4, 128
+    M_max, total, window = 21, 250, 100
+    budget = int(round(0.4 * (total - window)))
+    E, T = total - window - budget, 640
+    sbs, cap = _pair(B, Nb, Hq, Hkv, d, M_max, budget, window, E, mode)
+    sbs.prefill(_bf16(rng, Nb, Hkv, M_max, d), _bf16(rng, Nb, Hkv, M_max, d), [21, 9])
+    lens = []
+    for t in range(1, T + 1):
+        sbs.step(_bf16(rng, Nb, Hq, d, scale=1.5), _bf16(rng, Nb, Hkv, d), _bf16(rng, Nb, Hkv, d),
+                 check_scores=(t % 45 == 0))
+        lens.append(int(sbs.o.seq_len[0]))
+    sbs.check_scores()
+    sbs.check_state()
+    assert sbs.evictions == (T - total) // E + 1
+    assert max(lens) == 21 + total - 1 and min(lens[total:]) == 21 + budget + window
+    assert int(sbs.c.status.item()) == 0
+
+
 def test_cfg1_full_trajectory(B):
     """Config 1 end to end: 512 steps, 22 evictions, planted critical keys."""
     wl = configs.get("cfg1")

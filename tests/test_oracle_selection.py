@@ -160,7 +160,10 @@ def test_cache_length_follows_effective_length_formula():
     """Sec. 5 "Notions": S_i = M + i - n_i K, n_i = max(0, floor(((M+i)-B)/K)+1), with the total
     budget B = M + budget + window + evict_every and eviction volume K = evict_every."""
     rng = np.random.default_rng(15)
-    for (M, budget, window, E, T) in [(5, 8, 4, 2, 60), (3, 6, 3, 3, 50), (0, 4, 0, 4, 40), (7, 16, 8, 8, 100)]:
+    # (the last three have budget + window not a multiple of the period, as the paper's own settings do:
+    # total 5000, window 2000, retention 0.4 of the 3000 others => keep 1200, evict 1800 per trigger)
+    for (M, budget, window, E, T) in [(5, 8, 4, 2, 60), (3, 6, 3, 3, 50), (0, 4, 0, 4, 40), (7, 16, 8, 8, 100),
+                                      (5, 7, 4, 3, 60), (10, 12, 20, 18, 150), (4, 6, 10, 14, 120)]:
         lay, lens, events = _run_schedule(M, budget, window, E, T, rng)
         Bp = M + budget + window + E
         for i, got in enumerate(lens, start=1):
@@ -169,7 +172,7 @@ def test_cache_length_follows_effective_length_formula():
             assert orc.eviction_events(M, i, Bp, E) == n_i
             assert orc.effective_length(M, i, Bp, E) == got
             assert got - M <= budget + window + E - 1 or got - M == budget + window
-        assert events == (T - (budget + window)) // E
+        assert events == max(0, (T - (budget + window + E)) // E + 1)
         assert max(lens) < Bp
         # prompt never evicted, positions strictly increasing, local window = most recent tokens
         n = lens[-1]
