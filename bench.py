@@ -114,6 +114,32 @@ def cache_len_before_step(wl, t):
     return wl.prompt + t - n_triggers_through(wl, t - 1) * wl.evict_every
 
 
+def read_stream_rates(B, nbytes, dev):
+    """GB/s of the library's plain read-stream probe on buffers of nbytes: the same buffer again and again
+    (what a cache re-read every step can get from the memory-side cache) and a rotation of buffers that
+    together exceed it (what HBM alone delivers).  Median of 20 launches each, best of three grid sizes."""
+    import torch
+    n_rot = max(2, (2 << 30) // nbytes)
+    bufs = [torch.ones(nbytes // 4, dtype=torch.int32, device=dev) for _ in range(n_rot)]
+    sink = torch.zeros(4, dtype=torch.int32, device=dev)
+    ev = HipEvents(1)
+    a, b = ev.pairs[0]
+    best = {"same_buffer": 0.0, "rotating_buffers": 0.0}
+    for grid in (512, 1024, 2048):
+        for mode in best:
+            ts = []
+            for it in range(24):
+                buf = bufs[0] if mode == "same_buffer" else bufs[it % n_rot]
+                B.dynts_probe_read_stream(buf, grid, sink, a, b)
+                torch.cuda.synchronize()
+                if it >= 4:
+                    ts.append(ev.elapsed_ms(0))
+            ts.sort()
+            best[mode] = max(best[mode], nbytes / (ts[len(ts) // 2] * 1e-3) / 1e9)
+    ev.close()
+    return {k: round(v, 1) for k, v in best.items()}
+
+
 def run_gpu(args, wl):
     import torch
     from paper_2601_18383_amd import binding as B, synth
@@ -199,11 +225,13 @@ def run_gpu(args, wl):
         for ln in open(tf):
             if ln.startswith("hbm_bytes_per_launch:"):
                 traffic = int(ln.split(":")[1])
+    stream = read_stream_rates(B, int(bytes_launch) // 16 * 16, dev)
     roofline = {"bound": "hbm", "kernel": "attend_kernel<%d,attend,pending,append>" % wl.head_dim,
                 "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
                 "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": traffic,
                 "kernel_avg_us": round(k_avg_ms * 1e3, 2), "algorithmic_bytes_per_launch": int(bytes_launch),
-                "launches_timed": len(k_ms)}
+                "launches_timed": len(k_ms), "plain_read_stream_GBps": stream,
+                "frac_of_plain_read_stream": round(achieved / max(stream.values()), 4)}
     act_counts = [int(at_host[i].sum()) for i in range(args.steps)]
     step_bytes = sum(algorithmic_bytes(wl, [cache_len_before_step(wl, t + args.warmup + 1 + i)] * act_counts[i],
                                        act_counts[i]) for i in range(args.steps)) * L
@@ -312,6 +340,27 @@ def run_cpu_baseline(wl, budget_s=15.0):
                       (done, ", incl. 1 select+compact" if done >= E else "", wl.name, n0, dt, wl.n_layers)}
 
 
+def result_line(args, wl, r, cpu):
+    """The one JSON object bench.py prints."""
+    line = {
+        "metric": "decode steps/sec (attn+score+evict), 1 MI355X", "value": round(r["value"], 2),
+        "unit": "decode steps/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": round(r["ms_per_step"], 5), "higher_is_better": True, "scaling": "weak",
+        "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": "%s: %d layer(s), batch %d, %d q / %d kv heads, head_dim %d, prompt %d, budget %d, "
+                               "window %d, evict every %d; %s, %d-%d of %d sequences active" %
+                               (wl.name, wl.n_layers, wl.batch, wl.n_q_heads, wl.n_kv_heads, wl.head_dim, wl.prompt,
+                                wl.budget, wl.window, wl.evict_every,
+                                "whole decode from the prompt" if args.trajectory else "steady state",
+                                r["active_min"], r["active_max"], wl.batch),
+                   "first_timed_step": r["first_timed_step"], "evictions_in_window": r["evictions_timed"],
+                   "sequence_steps_per_s": round(r["seq_steps_per_s"], 1),
+                   "whole_step_algorithmic_GBps": round(r["whole_step_gbs"], 1)},
+        "roofline": r["roofline"], "cpu_baseline": cpu,
+    }
+    return line
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -361,21 +410,7 @@ def main():
             dst.copy_(src)
         torch.cuda.synchronize()
     cpu = None if args.no_cpu_baseline else run_cpu_baseline(wl)
-    line = {
-        "metric": "decode steps/sec (attn+score+evict), 1 MI355X", "value": round(r["value"], 2),
-        "unit": "decode steps/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
-        "ms_per_step": round(r["ms_per_step"], 5), "higher_is_better": True, "scaling": "weak",
-        "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
-        "config": {"workload": "%s: %d layer(s), batch %d, %d q / %d kv heads, head_dim %d, prompt %d, budget %d, "
-                               "window %d, evict every %d; " + ("whole decode from the prompt" if args.trajectory else "steady state") +
-                               ", %d-%d of %d sequences active" %
-                               (wl.name, wl.n_layers, wl.batch, wl.n_q_heads, wl.n_kv_heads, wl.head_dim, wl.prompt,
-                                wl.budget, wl.window, wl.evict_every, r["active_min"], r["active_max"], wl.batch),
-                   "first_timed_step": r["first_timed_step"], "evictions_in_window": r["evictions_timed"],
-                   "sequence_steps_per_s": round(r["seq_steps_per_s"], 1),
-                   "whole_step_algorithmic_GBps": round(r["whole_step_gbs"], 1)},
-        "roofline": r["roofline"], "cpu_baseline": cpu,
-    }
+    line = result_line(args, wl, r, cpu)
     print(json.dumps(line), flush=True)
 
 

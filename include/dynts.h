@@ -174,6 +174,15 @@ int dynts_set_kernel_events(dynts_ctx *ctx, void *start, void *stop);
  * each, after which the hook is off again.  n = 0 clears the list. */
 int dynts_set_kernel_event_list(dynts_ctx *ctx, void *const *starts, void *const *stops, int32_t n);
 
+/* Measurement aid, not part of the method: one launch of a plain read stream over `bytes` (a multiple
+ * of 16, buf 16-byte aligned) of device memory, 16 bytes per lane per load, n_workgroups x 256 lanes,
+ * grid-stride.  Nothing is written unless the XOR of all words equals `magic` (then sink[0], one
+ * device uint32, receives it).  start/stop: hipEvent_t handles attached to the dispatch as in
+ * dynts_set_kernel_events, or both NULL.  Its rate on a buffer of the cache's size is the bandwidth
+ * the simplest kernel reaches, to set beside the published peak. */
+int dynts_probe_read_stream(const void *buf, size_t bytes, int32_t n_workgroups, uint32_t magic,
+                            uint32_t *sink, void *start, void *stop, void *stream);
+
 #ifdef __cplusplus
 }
 #endif

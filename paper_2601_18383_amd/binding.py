@@ -21,7 +21,7 @@ EXPORTS = [
     "dynts_version", "dynts_strerror", "dynts_create", "dynts_destroy", "dynts_workspace_bytes",
     "dynts_bind", "dynts_prefill", "dynts_append", "dynts_decode_attend", "dynts_update_scores",
     "dynts_decode_attend_update", "dynts_decode_step", "dynts_select_evict", "dynts_compact",
-    "dynts_decode_loop", "dynts_set_kernel_events", "dynts_set_kernel_event_list",
+    "dynts_decode_loop", "dynts_set_kernel_events", "dynts_set_kernel_event_list", "dynts_probe_read_stream",
 ]
 
 
@@ -58,6 +58,7 @@ def _load():
     lib.dynts_decode_loop.argtypes = [vp, i32, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp, vp, vp]
     lib.dynts_set_kernel_events.argtypes = [vp, vp, vp]
     lib.dynts_set_kernel_event_list.argtypes = [vp, C.POINTER(vp), C.POINTER(vp), i32]
+    lib.dynts_probe_read_stream.argtypes = [vp, sz, i32, C.c_uint32, vp, vp, vp, vp]
     for name in EXPORTS:
         getattr(lib, name)
     return lib
@@ -201,6 +202,13 @@ def dynts_set_kernel_event_list(ctx, starts, stops):
     a = arr(*[s.value if isinstance(s, C.c_void_p) else s for s in starts]) if n else None
     b = arr(*[s.value if isinstance(s, C.c_void_p) else s for s in stops]) if n else None
     _check(lib.dynts_set_kernel_event_list(ctx, a, b, n), "dynts_set_kernel_event_list")
+
+
+def dynts_probe_read_stream(buf, n_workgroups, sink, start=None, stop=None, magic=0x9E3779B9, stream=None):
+    """buf: contiguous device tensor (its byte size a multiple of 16); sink: device tensor of >= 4 bytes."""
+    nbytes = buf.numel() * buf.element_size()
+    _check(lib.dynts_probe_read_stream(buf.data_ptr(), nbytes, n_workgroups, magic, sink.data_ptr(), start, stop,
+                                       _stream(stream)), "dynts_probe_read_stream")
 
 
 class Cache:

@@ -1,8 +1,10 @@
 // Decode attention + deferred importance-score accumulation for gfx950 (wave64, MFMA).
 //
-// One workgroup (4 waves) owns a contiguous chunk of one (sequence, KV head) cache; its waves
-// walk the chunk's 32-slot tiles in turn, each wave with the next tile's loads already in
-// flight while it works on the current one:
+// The cache of one (sequence, KV head) is shared out over nsplit workgroups of W waves (8 by
+// default).  Wave number wi of the nsplit*W takes the 32-slot tile that starts at slot 32*wi -- its
+// loads are issued before the kernel knows the sequence length -- and then an equal, contiguous
+// share of the slots behind those first tiles, 32 at a time, with the next tile's loads already
+// in flight while it works on the current one:
 //   * K rows go straight from HBM into MFMA operand registers (16-byte loads; lane (r, kg)
 //     holds row r, columns 32*ks + 8*kg .. +7).  One v_mfma_f32_16x16x32_bf16 per 32 columns
 //     gives the logits of 16 slots x 16 (padded) query heads of the group, so a K tile is read
@@ -16,17 +18,19 @@
 //     ds_read_b64_tr_b16 transposing reads out) to form the V^T MFMA operand; the softmax
 //     weights are split into bf16 hi + lo parts so P.V keeps ~16 bits of each weight
 //     (Eq. attn-o); accumulation is fp32 throughout.
-//   * online-softmax state (running max, sum, output) is per wave; the four waves are combined
-//     in LDS.  A chunk that is the whole cache is finished on the spot; otherwise the partial
+//   * online-softmax state (running max, sum, output) is per wave; the waves of a workgroup are
+//     combined in LDS.  With nsplit == 1 the result is finished on the spot; otherwise the partial
 //     goes to the workspace and the LAST workgroup of the (sequence, KV head) to arrive
 //     (device-scope counter) merges the partials, writes `out`, and saves the query and the
-//     statistics that the next step's score update needs.  The last workgroup of a sequence
-//     advances seq_len / next_pos.  No second kernel, no host round trip.
+//     statistics that the next step's score update needs.  Every workgroup checks in on a
+//     per-sequence counter as it starts; the last one to do so advances seq_len / next_pos.
+//     No second kernel, no host round trip.
+//   * with APPEND the new token's K/V row is written to its slot by one workgroup and enters the
+//     softmax as the initial state of the first wave (max = q.k_new, sum = 1, output = v_new), so
+//     no wave has to wait for the row to become visible.
 #pragma once
 #include <hip/hip_runtime.h>
 #include <stdint.h>
-
-#include <type_traits>
 
 namespace dynts {
 

@@ -13,6 +13,7 @@
 
 #include "attend.hpp"
 #include "compact.hpp"
+#include "probe.hpp"
 #include "select.hpp"
 
 namespace {
@@ -429,6 +430,18 @@ int dynts_set_kernel_event_list(dynts_ctx *ctx, void *const *starts, void *const
     ctx->ev_list_stop.push_back(static_cast<hipEvent_t>(stops[i]));
   }
   return DYNTS_OK;
+}
+
+int dynts_probe_read_stream(const void *buf, size_t bytes, int32_t n_workgroups, uint32_t magic, uint32_t *sink,
+                            void *start, void *stop, void *stream) {
+  if (!buf || !sink) return DYNTS_ENULL;
+  if (bytes == 0 || bytes % 16 != 0 || n_workgroups <= 0 || n_workgroups > (1 << 20)) return DYNTS_EINVAL;
+  if ((reinterpret_cast<uintptr_t>(buf) & 15) != 0) return DYNTS_EINVAL;
+  if ((start == nullptr) != (stop == nullptr)) return DYNTS_EINVAL;
+  hipExtLaunchKernelGGL(dynts::read_stream_kernel, dim3(n_workgroups), dim3(dynts::kProbeThreads), 0,
+                        static_cast<hipStream_t>(stream), static_cast<hipEvent_t>(start),
+                        static_cast<hipEvent_t>(stop), 0, static_cast<const uint32_t *>(buf), bytes / 16, magic, sink);
+  return launch_status();
 }
 
 int dynts_decode_loop(dynts_ctx *ctx, int32_t n_steps, const uint16_t *q, const uint16_t *k_new,

@@ -112,3 +112,47 @@ def test_missing_library_is_an_import_error(monkeypatch, tmp_path):
         importlib.reload(binding)
     monkeypatch.delenv("DYNTS_LIBRARY")
     importlib.reload(binding)
+
+
+def test_bench_result_line_has_the_contract_fields():
+    """bench.py's output object, formatted from stand-in numbers (no GPU): every field of the contract."""
+    import argparse
+    import json
+    import bench
+    from paper_2601_18383_amd import configs
+    wl = configs.get("cfg3")
+    r = dict(value=1.0, ms_per_step=1.0, roofline={"bound": "hbm", "achieved": 1.0, "peak": 8000.0, "unit": "GB/s",
+                                                    "frac": 0.1, "traffic": None},
+             whole_step_gbs=1.0, seq_steps_per_s=1.0, evictions_timed=1, first_timed_step=1, active_min=1,
+             active_max=2)
+    for traj in (False, True):
+        args = argparse.Namespace(steps=4, warmup=1, trajectory=traj)
+        line = json.loads(json.dumps(bench.result_line(args, wl, r, None)))
+        for key in ("metric", "value", "unit", "n_gpus", "steps", "warmup", "ms_per_step", "higher_is_better",
+                    "scaling", "vs_baseline", "dtype", "data", "config", "roofline", "cpu_baseline"):
+            assert key in line
+        assert "workload" in line["config"] and "model" not in line["config"]
+
+
+def test_bench_trigger_schedule_matches_the_oracle_layer():
+    """bench.py's host-side schedule (trigger steps, cache length per step) against the oracle's own run."""
+    import bench
+    import numpy as np
+    from oracle import dynts_oracle as orc
+    from paper_2601_18383_amd import configs
+    import dataclasses
+    rng = np.random.default_rng(0)
+    for (M, budget, window, E) in [(3, 8, 4, 4), (5, 6, 10, 9), (2, 4, 12, 7)]:
+        wl = dataclasses.replace(configs.get("cfg1"), prompt=M, budget=budget, window=window, evict_every=E)
+        lay = orc.OracleLayer(1, 2, 1, 4, wl.capacity, budget, window, E)
+        lay.prefill(rng.standard_normal((1, 1, M, 4)), rng.standard_normal((1, 1, M, 4)), [M])
+        T = 90
+        flags = bench.evict_flags(wl, 0, T)
+        for t in range(1, T + 1):
+            lay.append(rng.standard_normal((1, 1, 4)), rng.standard_normal((1, 1, 4)))
+            assert int(lay.seq_len[0]) == bench.cache_len_before_step(wl, t)
+            trig = lay.due()
+            assert int(trig[0]) == int(flags[t - 1])
+            if trig[0]:
+                keep, new_len = lay.select(trig)
+                lay.compact(keep, new_len, trig)
