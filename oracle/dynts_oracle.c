@@ -161,6 +161,62 @@ int dynts_oracle_update_scores(int Nb, int Hq, int Hkv, int cap, const double *a
   return 0;
 }
 
+/*
+ * Importance score from a block of queries at once (Eq. importance-score with
+ * its sum over the K answer tokens written out; App. B.1 extracts the
+ * answer-by-thinking sub-matrix of the attention weights of one forward pass
+ * and sums it over heads and over the answer dimension).
+ *   q_blk [Nb][T][Hq][d]   the T block queries a_1..a_T of every query head
+ *   k_blk [Nb][T][Hkv][d]  their own keys, or NULL
+ * Query i attends to the seq_len[b] cached slots and, when k_blk is given, to
+ * block keys 0..i (causal, as in the forward pass the paper describes); the
+ * softmax of Eq. attn-score runs over exactly those.  For every cached slot j
+ *   I[b][h][j] += sum_{i<T} sum_{g in group of h} alpha_{(i,g), j}
+ * (I [Nb][Hkv][cap], question and thinking slots alike; block tokens themselves
+ * receive no score).
+ */
+int dynts_oracle_score_block(int Nb, int T, int Hq, int Hkv, int d, int cap,
+                             const double *q_blk, const double *k_blk, const double *K,
+                             const int32_t *seq_len, const uint8_t *active, double scale,
+                             double *I) {
+  if (Nb <= 0 || T <= 0 || Hq <= 0 || Hkv <= 0 || d <= 0 || cap <= 0 || Hq % Hkv) return -1;
+  const int G = Hq / Hkv;
+  int bad = 0;
+#pragma omp parallel for schedule(dynamic, 1)
+  for (int u = 0; u < Nb * Hkv; ++u) {
+    int b = u / Hkv, h = u % Hkv;
+    if (active && !active[b]) continue;
+    int n = seq_len[b];
+    if (n < 0 || n > cap) { bad = 1; continue; }
+    const double *Ku = K + (size_t)u * cap * d;
+    double *Iu = I + (size_t)u * cap;
+    double *e = (double *)malloc(sizeof(double) * (size_t)(n + T));
+    for (int i = 0; i < T; ++i) {
+      int vis = k_blk ? i + 1 : 0; /* block keys this query sees */
+      for (int g = 0; g < G; ++g) {
+        const double *qv = q_blk + (((size_t)b * T + i) * Hq + (size_t)h * G + g) * d;
+        double m = -INFINITY;
+        for (int j = 0; j < n + vis; ++j) {
+          const double *kv = j < n ? Ku + (size_t)j * d
+                                   : k_blk + (((size_t)b * T + (j - n)) * Hkv + h) * d;
+          double acc = 0.0;
+          for (int c = 0; c < d; ++c) acc += qv[c] * kv[c];
+          e[j] = acc * scale;
+          if (e[j] > m) m = e[j];
+        }
+        double l = 0.0;
+        for (int j = 0; j < n + vis; ++j) {
+          e[j] = exp(e[j] - m);
+          l += e[j];
+        }
+        for (int j = 0; j < n; ++j) Iu[j] += e[j] / l;
+      }
+    }
+    free(e);
+  }
+  return bad ? -1 : 0;
+}
+
 /* ---- selection ---------------------------------------------------------- */
 
 typedef struct {

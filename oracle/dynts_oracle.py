@@ -86,6 +86,19 @@ def update_scores(S, alpha, seq_len, n_prompt, active=None):
            "update_scores")
 
 
+def score_block(q_blk, k_blk, K, seq_len, scale, active=None, I=None):
+    """Eq. importance-score for a block of queries: q_blk [Nb][T][Hq][d], k_blk [Nb][T][Hkv][d] or None
+    (the block's own keys, seen causally).  Returns I [Nb][Hkv][cap] (added to the I passed in, if any)."""
+    Nb, T, Hq, d = q_blk.shape
+    _, Hkv, cap, _ = K.shape
+    if I is None:
+        I = np.zeros((Nb, Hkv, cap), _f64)
+    _check(lib().dynts_oracle_score_block(Nb, T, Hq, Hkv, d, cap, _p(q_blk, _f64), _p(k_blk, _f64), _p(K, _f64),
+                                          _p(seq_len, _i32), _p(active, _u8), C.c_double(scale), _p(I, _f64)),
+           "score_block")
+    return I
+
+
 def select(S, pos, seq_len, n_prompt, window, k_keep, trigger=None, keep_stride=None):
     """Returns (keep_idx [Nb][Hkv][keep_stride] (-1 padded), new_len [Nb])."""
     Nb, Hkv, cap = S.shape
@@ -177,6 +190,15 @@ class OracleLayer:
     def update_scores(self, alpha, active=None):
         if not self.external:
             update_scores(self.S, alpha, self.seq_len, self.n_prompt, active)
+
+    def score_block(self, q_blk, k_blk=None, active=None):
+        """Add the block's attention (Eq. importance-score) to the scores of the thinking slots."""
+        I = score_block(q_blk, k_blk, self.K, self.seq_len, self.scale, active)
+        for b in range(self.Nb):
+            if active is not None and not active[b]:
+                continue
+            self.S[b, :, self.n_prompt[b]:self.seq_len[b]] += I[b, :, self.n_prompt[b]:self.seq_len[b]]
+        return I
 
     def due(self, active=None):
         """Trigger mask after a step: the cache has reached its total budget (Sec. 4.2).  Sec. 5 counts
