@@ -174,6 +174,26 @@ int dynts_set_kernel_events(dynts_ctx *ctx, void *start, void *stop);
  * each, after which the hook is off again.  n = 0 clears the list. */
 int dynts_set_kernel_event_list(dynts_ctx *ctx, void *const *starts, void *const *stops, int32_t n);
 
+/* Importance score from a block of queries at once (Eq. importance-score with its sum over the K
+ * answer tokens; App. B.1: the answer-by-thinking sub-matrix of the attention weights summed over
+ * heads and over the answer dimension):
+ *   dst[b][h][j] (+)= sum over the n_queries block queries i and the G heads g of the group of
+ *                    alpha_{(i,g), j},   for the cached slots j < seq_len[b],
+ * where query i's softmax (Eq. attn-score) runs over the cached slots and, when k_blk is given, over
+ * block keys 0..i (causal, as in one forward pass over the block; block tokens receive no score).
+ *   q_blk bf16 [Nb][n_queries][Hq][d]     k_blk bf16 [Nb][n_queries][Hkv][d] or NULL
+ *   dst fp32 [Nb][Hkv][cap]: every slot j < seq_len[b] is written (question slots too).  dst = NULL
+ *     means the layer's score array S; then slots below n_prompt[b] keep their +inf.
+ *   accumulate != 0 adds to dst, 0 overwrites it.
+ *   scratch: >= dynts_score_block_scratch_bytes(cfg, n_queries) bytes of device memory, 4-byte
+ *     aligned, contents irrelevant before and after.
+ * Independent of the deferred accumulation of the fused decode calls (sums commute).  The cache is
+ * only read. */
+size_t dynts_score_block_scratch_bytes(const dynts_config *cfg, int32_t n_queries);
+int dynts_score_block(dynts_ctx *ctx, int32_t layer, const uint16_t *q_blk, const uint16_t *k_blk,
+                      int32_t n_queries, const uint8_t *active, float *dst, int32_t accumulate,
+                      void *scratch, size_t scratch_bytes, void *stream);
+
 /* Measurement aid, not part of the method: one launch of a plain read stream over `bytes` (a multiple
  * of 16, buf 16-byte aligned) of device memory, 16 bytes per lane per load, n_workgroups x 256 lanes,
  * grid-stride.  Nothing is written unless the XOR of all words equals `magic` (then sink[0], one

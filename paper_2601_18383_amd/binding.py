@@ -22,6 +22,7 @@ EXPORTS = [
     "dynts_bind", "dynts_prefill", "dynts_append", "dynts_decode_attend", "dynts_update_scores",
     "dynts_decode_attend_update", "dynts_decode_step", "dynts_select_evict", "dynts_compact",
     "dynts_decode_loop", "dynts_set_kernel_events", "dynts_set_kernel_event_list", "dynts_probe_read_stream",
+    "dynts_score_block_scratch_bytes", "dynts_score_block",
 ]
 
 
@@ -58,6 +59,9 @@ def _load():
     lib.dynts_decode_loop.argtypes = [vp, i32, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp, vp, vp]
     lib.dynts_set_kernel_events.argtypes = [vp, vp, vp]
     lib.dynts_set_kernel_event_list.argtypes = [vp, C.POINTER(vp), C.POINTER(vp), i32]
+    lib.dynts_score_block_scratch_bytes.restype = sz
+    lib.dynts_score_block_scratch_bytes.argtypes = [C.POINTER(dynts_config), i32]
+    lib.dynts_score_block.argtypes = [vp, i32, vp, vp, i32, vp, vp, i32, vp, sz, vp]
     lib.dynts_probe_read_stream.argtypes = [vp, sz, i32, C.c_uint32, vp, vp, vp, vp]
     for name in EXPORTS:
         getattr(lib, name)
@@ -202,6 +206,20 @@ def dynts_set_kernel_event_list(ctx, starts, stops):
     a = arr(*[s.value if isinstance(s, C.c_void_p) else s for s in starts]) if n else None
     b = arr(*[s.value if isinstance(s, C.c_void_p) else s for s in stops]) if n else None
     _check(lib.dynts_set_kernel_event_list(ctx, a, b, n), "dynts_set_kernel_event_list")
+
+
+def dynts_score_block_scratch_bytes(cfg, n_queries):
+    return int(lib.dynts_score_block_scratch_bytes(C.byref(cfg), n_queries))
+
+
+def dynts_score_block(ctx, layer, q_blk, k_blk, scratch, dst=None, accumulate=True, active=None, stream=None):
+    """q_blk bf16 [Nb][T][Hq][d], k_blk bf16 [Nb][T][Hkv][d] or None, scratch: device uint8/any tensor of
+    at least dynts_score_block_scratch_bytes bytes; dst fp32 [Nb][Hkv][cap] or None (= the layer's S)."""
+    T = q_blk.shape[1]
+    _check(lib.dynts_score_block(ctx, layer, _ptr(q_blk, torch.bfloat16), _ptr(k_blk, torch.bfloat16), T,
+                                 _ptr(active, torch.uint8), _ptr(dst, torch.float32), 1 if accumulate else 0,
+                                 scratch.data_ptr(), scratch.numel() * scratch.element_size(), _stream(stream)),
+           "dynts_score_block")
 
 
 def dynts_probe_read_stream(buf, n_workgroups, sink, start=None, stop=None, magic=0x9E3779B9, stream=None):

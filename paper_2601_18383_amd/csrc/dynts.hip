@@ -14,6 +14,7 @@
 #include "attend.hpp"
 #include "compact.hpp"
 #include "probe.hpp"
+#include "score_block.hpp"
 #include "select.hpp"
 
 namespace {
@@ -430,6 +431,57 @@ int dynts_set_kernel_event_list(dynts_ctx *ctx, void *const *starts, void *const
     ctx->ev_list_stop.push_back(static_cast<hipEvent_t>(stops[i]));
   }
   return DYNTS_OK;
+}
+
+size_t dynts_score_block_scratch_bytes(const dynts_config *cfg, int32_t n_queries) {
+  if (!cfg || check_config(cfg) != DYNTS_OK || n_queries <= 0 || n_queries > (1 << 20)) return 0;
+  const size_t rpad = align_up((size_t)n_queries * (cfg->n_q_heads / cfg->n_kv_heads));
+  return align_up((size_t)cfg->batch * cfg->n_kv_heads * rpad * sizeof(float));
+}
+
+int dynts_score_block(dynts_ctx *ctx, int32_t layer, const uint16_t *q_blk, const uint16_t *k_blk,
+                      int32_t n_queries, const uint8_t *active, float *dst, int32_t accumulate, void *scratch,
+                      size_t scratch_bytes, void *stream) {
+  int rc = check_call(ctx, layer);
+  if (rc != DYNTS_OK) return rc;
+  if (!q_blk || !scratch) return DYNTS_ENULL;
+  if (n_queries <= 0 || n_queries > (1 << 20)) return DYNTS_EINVAL;
+  if (reinterpret_cast<uintptr_t>(q_blk) % 16 || reinterpret_cast<uintptr_t>(k_blk) % 16) return DYNTS_EINVAL;
+  const dynts_config &c = ctx->cfg;
+  const size_t need = dynts_score_block_scratch_bytes(&c, n_queries);
+  if (scratch_bytes < need || reinterpret_cast<uintptr_t>(scratch) % 4) return DYNTS_EWORKSPACE;
+  const LayerView lv = layer_view(ctx, layer);
+  const int G = c.n_q_heads / c.n_kv_heads;
+  dynts::ScoreBlockParams p{};
+  p.K = lv.K;
+  p.q_blk = q_blk;
+  p.k_blk = k_blk;
+  p.seq_len = lv.seq_len;
+  p.n_prompt = ctx->n_prompt;
+  p.active = active;
+  p.stats = static_cast<float *>(scratch);
+  p.dst = dst ? dst : lv.S;
+  p.T = n_queries;
+  p.Hq = c.n_q_heads;
+  p.Hkv = c.n_kv_heads;
+  p.G = G;
+  p.cap = c.capacity;
+  p.Rpad = (int)align_up((size_t)n_queries * G);
+  p.skip_prompt = dst ? 0 : 1;
+  p.accumulate = accumulate ? 1 : 0;
+  p.scale_log2 = ctx->scale_log2;
+  const long long R = (long long)n_queries * G;
+  const dim3 g1((unsigned)((R + dynts::kSbRowsPerWg - 1) / dynts::kSbRowsPerWg), c.n_kv_heads, c.batch);
+  const dim3 g2((unsigned)((c.capacity + dynts::kSbRowsPerWg - 1) / dynts::kSbRowsPerWg), c.n_kv_heads, c.batch);
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  if (c.head_dim == 128) {
+    hipLaunchKernelGGL(dynts::score_block_stats_kernel<128>, g1, dim3(dynts::kSbWaves * 64), 0, st, p);
+    hipLaunchKernelGGL(dynts::score_block_colsum_kernel<128>, g2, dim3(dynts::kSbWaves * 64), 0, st, p);
+  } else {
+    hipLaunchKernelGGL(dynts::score_block_stats_kernel<64>, g1, dim3(dynts::kSbWaves * 64), 0, st, p);
+    hipLaunchKernelGGL(dynts::score_block_colsum_kernel<64>, g2, dim3(dynts::kSbWaves * 64), 0, st, p);
+  }
+  return launch_status();
 }
 
 int dynts_probe_read_stream(const void *buf, size_t bytes, int32_t n_workgroups, uint32_t magic, uint32_t *sink,
