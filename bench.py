@@ -294,6 +294,54 @@ def run_trajectory(args, wl):
                 first_timed_step=1, active_min=int(act_host[-1].sum()), active_max=wl.batch, steps=t_max)
 
 
+def run_score_block(args, wl):
+    """Block scoring (Eq. importance-score over a block of T answer queries with their own keys) on a
+    generator-made steady-state cache of layer 0: both kernels of one call, timed with events on the
+    launch stream.  A step is one call on the full batch."""
+    import torch
+    from paper_2601_18383_amd import binding as B, synth
+
+    dev = torch.device("cuda:0")
+    gen = synth.Synth(wl, dev)
+    cache = B.Cache.for_workload(wl, device=dev)
+    T, n0 = args.score_block, wl.steady_len + wl.evict_every // 2
+    st = gen.steady_state(0, n0)
+    cache.K[0, :, :, :n0] = st["K"]
+    cache.S[0, :, :, :n0] = st["S"]
+    cache.seq_len[0].fill_(n0)
+    cache.n_prompt.fill_(wl.prompt)
+    steps = torch.arange(70000, 70000 + T)
+    q = gen.q(0, steps).permute(1, 0, 2, 3).contiguous()
+    kb = gen.kv(0, steps)[0].permute(1, 0, 2, 3).contiguous()
+    scratch = torch.empty(B.dynts_score_block_scratch_bytes(cache.cfg, T), dtype=torch.uint8, device=dev)
+    dst = torch.zeros((wl.batch, wl.n_kv_heads, wl.capacity), dtype=torch.float32, device=dev)
+    for _ in range(args.warmup):
+        B.dynts_score_block(cache.ctx, 0, q, kb, scratch, dst=dst, accumulate=False)
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    t0 = time.perf_counter()
+    e0.record()
+    for _ in range(args.steps):
+        B.dynts_score_block(cache.ctx, 0, q, kb, scratch, dst=dst, accumulate=False)
+    e1.record()
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    ev_ms = e0.elapsed_time(e1) / args.steps
+    units, R, d = wl.batch * wl.n_kv_heads, T * wl.group, wl.head_dim
+    # the contraction the method defines: every query row against the cached slots and its visible block keys
+    flops = units * 2.0 * d * (R * n0 + wl.group * T * (T + 1) / 2)
+    executed = units * 2.0 * d * (2 * R * n0 + wl.group * T * (T + 1) / 2)   # the logits are formed twice
+    peak = 2500.0
+    roofline = {"bound": "mfma", "kernel": "score_block_stats_kernel + score_block_colsum_kernel",
+                "achieved": round(flops / (ev_ms * 1e-3) / 1e12, 1), "peak": peak, "unit": "TFLOP/s",
+                "frac": round(flops / (ev_ms * 1e-3) / 1e12 / peak, 4), "traffic": None,
+                "call_avg_us": round(ev_ms * 1e3, 1), "algorithmic_flops_per_call": flops,
+                "executed_mfma_flops_per_call": executed, "exp2_per_call": units * (2.0 * R * n0)}
+    return dict(value=args.steps / dt, ms_per_step=dt / args.steps * 1e3, roofline=roofline,
+                whole_step_gbs=0.0, seq_steps_per_s=args.steps * wl.batch / dt, evictions_timed=0,
+                first_timed_step=0, active_min=wl.batch, active_max=wl.batch)
+
+
 def run_cpu_baseline(wl, budget_s=15.0):
     """The float64 oracle, as it stands, on the host cores: whole decode steps of the same
     workload from a generator-made steady state (one layer's worth scaled to all layers)."""
@@ -343,14 +391,17 @@ def run_cpu_baseline(wl, budget_s=15.0):
 def result_line(args, wl, r, cpu):
     """The one JSON object bench.py prints."""
     line = {
-        "metric": "decode steps/sec (attn+score+evict), 1 MI355X", "value": round(r["value"], 2),
-        "unit": "decode steps/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "metric": "block-scoring calls/sec, 1 MI355X" if getattr(args, "score_block", 0) else
+                  "decode steps/sec (attn+score+evict), 1 MI355X", "value": round(r["value"], 2),
+        "unit": "calls/s" if getattr(args, "score_block", 0) else "decode steps/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": round(r["ms_per_step"], 5), "higher_is_better": True, "scaling": "weak",
         "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
         "config": {"workload": "%s: %d layer(s), batch %d, %d q / %d kv heads, head_dim %d, prompt %d, budget %d, "
                                "window %d, evict every %d; %s, %d-%d of %d sequences active" %
                                (wl.name, wl.n_layers, wl.batch, wl.n_q_heads, wl.n_kv_heads, wl.head_dim, wl.prompt,
                                 wl.budget, wl.window, wl.evict_every,
+                                "block scoring of %d queries per sequence on a steady-state cache" % args.score_block
+                                if getattr(args, "score_block", 0) else
                                 "whole decode from the prompt" if args.trajectory else "steady state",
                                 r["active_min"], r["active_max"], wl.batch),
                    "first_timed_step": r["first_timed_step"], "evictions_in_window": r["evictions_timed"],
@@ -374,6 +425,9 @@ def main():
                     help="time the whole decode from the prompt to the end of the longest sequence (ragged "
                          "batches decay) instead of a steady-state window; --steps/--warmup are ignored")
     ap.add_argument("--max-steps", type=int, default=0, help="with --trajectory: stop after this many steps")
+    ap.add_argument("--score-block", type=int, default=0, metavar="T",
+                    help="time dynts_score_block for a block of T queries (with their keys) on a steady-state "
+                         "cache instead of the decode path")
     ap.add_argument("--full-kv", action="store_true",
                     help="the comparison run without eviction: same inputs, a cache that holds every token, "
                          "attention only (no score is kept)")
@@ -397,7 +451,10 @@ def main():
                                  evict_every=1, external_scores=True)
         args.trajectory = True
     log("host cores: %d; workload %s" % (os.cpu_count(), wl))
-    if args.trajectory:
+    if args.score_block:
+        r = run_score_block(args, wl)
+        args.no_cpu_baseline = True
+    elif args.trajectory:
         r = run_trajectory(args, wl)
         args.steps, args.warmup, args.no_cpu_baseline = r["steps"], 0, True
     else:

@@ -461,6 +461,7 @@ int dynts_score_block(dynts_ctx *ctx, int32_t layer, const uint16_t *q_blk, cons
   p.active = active;
   p.stats = static_cast<float *>(scratch);
   p.dst = dst ? dst : lv.S;
+  p.Nb = c.batch;
   p.T = n_queries;
   p.Hq = c.n_q_heads;
   p.Hkv = c.n_kv_heads;
@@ -471,8 +472,13 @@ int dynts_score_block(dynts_ctx *ctx, int32_t layer, const uint16_t *q_blk, cons
   p.accumulate = accumulate ? 1 : 0;
   p.scale_log2 = ctx->scale_log2;
   const long long R = (long long)n_queries * G;
-  const dim3 g1((unsigned)((R + dynts::kSbRowsPerWg - 1) / dynts::kSbRowsPerWg), c.n_kv_heads, c.batch);
-  const dim3 g2((unsigned)((c.capacity + dynts::kSbRowsPerWg - 1) / dynts::kSbRowsPerWg), c.n_kv_heads, c.batch);
+  // (1-D grids: blocks per unit x units rounded up to the 8 XCDs, mapped inside the kernels)
+  const long long units8 = ((long long)c.batch * c.n_kv_heads + 7) / 8 * 8;
+  const long long b1 = (R + dynts::kSbRowsPerWg - 1) / dynts::kSbRowsPerWg;
+  const long long b2 = (c.capacity + dynts::kSbRowsPerWg - 1) / dynts::kSbRowsPerWg;
+  if (b1 * units8 > 0x7fffffffLL || b2 * units8 > 0x7fffffffLL) return DYNTS_EINVAL;
+  if ((long long)n_queries * c.n_q_heads * c.head_dim * 2 > 0x7fffffffLL) return DYNTS_EINVAL;  // 32-bit row offsets
+  const dim3 g1((unsigned)(b1 * units8)), g2((unsigned)(b2 * units8));
   hipStream_t st = static_cast<hipStream_t>(stream);
   if (c.head_dim == 128) {
     hipLaunchKernelGGL(dynts::score_block_stats_kernel<128>, g1, dim3(dynts::kSbWaves * 64), 0, st, p);

@@ -43,7 +43,7 @@ struct ScoreBlockParams {
   const uint8_t *active;    // [Nb] or null
   float *stats;             // [Nb][Hkv][Rpad]  log2 of the softmax denominator per query row
   float *dst;               // [Nb][Hkv][cap]
-  int T, Hq, Hkv, G, cap, Rpad;
+  int Nb, T, Hq, Hkv, G, cap, Rpad;
   int skip_prompt;          // 1: slots below n_prompt[b] are left alone (dst is the score array)
   int accumulate;           // 1: dst += sums, 0: dst = sums
   float scale_log2;         // softmax scale * log2(e)
@@ -51,43 +51,85 @@ struct ScoreBlockParams {
 
 // MFMA operand fragments of one row: 16 bytes per k-step at the lane's column group.
 template <int D>
-__device__ __forceinline__ void load_row_frags(bf16x8 (&f)[D / 32], const uint16_t *row, int kg) {
-  const char *base = reinterpret_cast<const char *>(row) + 16 * kg;
+__device__ __forceinline__ void load_row_frags(bf16x8 (&f)[D / 32], const char *row, int kg) {
+  const char *base = row + 16 * kg;
 #pragma unroll
   for (int ks = 0; ks < D / 32; ++ks)
     f[ks] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const u32x4 *>(base + 64 * ks));
 }
 
-// Address of query row r = i * G + g of the group of KV head h (rows beyond the last repeat it).
-template <int D>
-__device__ __forceinline__ const uint16_t *query_row(const ScoreBlockParams &p, int b, int h, int r, int R) {
-  r = r < R ? r : R - 1;
-  const int i = r / p.G, g = r - i * p.G;
-  return p.q_blk + (((size_t)b * p.T + i) * p.Hq + (size_t)h * p.G + g) * D;
+// Workgroup -> (unit, block).  Consecutive workgroup ids go to the 8 XCDs in turn; this mapping
+// keeps all blocks of one (sequence, KV head) unit on one XCD, so the operand they all stream is
+// fetched into one L2 instead of eight.  Returns false for the padding of the last group of units.
+__device__ __forceinline__ bool sb_map(int n_blk, int n_units, int &unit, int &blk) {
+  const int id = blockIdx.x, xcd = id & 7, slot = id >> 3;
+  unit = (slot / n_blk) * 8 + xcd;
+  blk = slot % n_blk;
+  return unit < n_units;
 }
 
+// A lane's walk over the query rows r = i * G + g of a KV head's group, 16 rows at a time.
+struct QueryWalk {
+  int r, i, g;
+  uint32_t off;         // byte offset of row (i, g) from the (sequence, head-group) base
+  int step_i, step_g;   // 16 = step_i * G + step_g
+  uint32_t stride_i, stride_g;
+  __device__ __forceinline__ void init(int r0, int G, int Hq, int D) {
+    r = r0;
+    i = r0 / G;
+    g = r0 - i * G;
+    step_i = 16 / G;
+    step_g = 16 - step_i * G;
+    stride_i = (uint32_t)Hq * D * 2;
+    stride_g = (uint32_t)D * 2;
+    off = (uint32_t)i * stride_i + (uint32_t)g * stride_g;
+  }
+  __device__ __forceinline__ void advance(int G) {
+    r += 16;
+    i += step_i;
+    g += step_g;
+    off += (uint32_t)step_i * stride_i + (uint32_t)step_g * stride_g;
+    if (g >= G) {
+      g -= G;
+      i += 1;
+      off += stride_i - (uint32_t)G * stride_g;
+    }
+  }
+};
+
 // ---- pass 1: log2 of the softmax denominator of every query row ---------------------------------
-// grid (ceil(R / 256), Hkv, Nb), 256 threads.
+// 1-D grid of ceil(R / 256) * round_up(units, 8) workgroups, 256 threads.
 template <int D>
 __global__ __launch_bounds__(kSbWaves * 64) void score_block_stats_kernel(const ScoreBlockParams p) {
   constexpr int KS = D / 32;
-  const int b = blockIdx.z, h = blockIdx.y;
+  const int R = p.T * p.G;
+  int unit, blk;
+  if (!sb_map((R + kSbRowsPerWg - 1) / kSbRowsPerWg, p.Nb * p.Hkv, unit, blk)) return;
+  const int b = unit / p.Hkv, h = unit - b * p.Hkv;
   if (p.active && !p.active[b]) return;
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int r16 = lane & 15, kg = lane >> 4;
-  const int R = p.T * p.G;
-  const int row0 = blockIdx.x * kSbRowsPerWg + wave * kSbRowsPerWave;
+  const int row0 = blk * kSbRowsPerWg + wave * kSbRowsPerWave;
   if (row0 >= R) return;
   int n = p.seq_len[b];
   n = n < 0 ? 0 : (n > p.cap ? p.cap : n);
-  const size_t unit = (size_t)b * p.Hkv + h;
-  const uint16_t *Kb = p.K + unit * (size_t)p.cap * D;
+  const char *Kb = reinterpret_cast<const char *>(p.K + (size_t)unit * (size_t)p.cap * D);
+  const char *Qb = reinterpret_cast<const char *>(p.q_blk + ((size_t)b * p.T * p.Hq + (size_t)h * p.G) * D);
+  const float c = p.scale_log2;
 
   // stationary: this wave's query rows (B operand: column r16 of tile qt is row row0 + 16 qt + r16)
   bf16x8 qf[kSbTiles][KS];
+  int vis_blk[kSbTiles];  // block keys [0, vis_blk) are visible to this lane's query column
 #pragma unroll
-  for (int qt = 0; qt < kSbTiles; ++qt) load_row_frags<D>(qf[qt], query_row<D>(p, b, h, row0 + 16 * qt + r16, R), kg);
+  for (int qt = 0; qt < kSbTiles; ++qt) {
+    int r = row0 + 16 * qt + r16;
+    r = r < R ? r : R - 1;
+    const int i = r / p.G, g = r - i * p.G;
+    vis_blk[qt] = i + 1;
+    load_row_frags<D>(qf[qt], Qb + ((size_t)i * p.Hq + g) * (size_t)(2 * D), kg);
+  }
 
+  // running max (in raw dot-product units) and sum of 2^(c * (dot - max)), private to the lane
   float m[kSbTiles], l[kSbTiles];
 #pragma unroll
   for (int qt = 0; qt < kSbTiles; ++qt) {
@@ -95,96 +137,95 @@ __global__ __launch_bounds__(kSbWaves * 64) void score_block_stats_kernel(const 
     l[qt] = 0.f;
   }
 
-  // one streamed tile: logits of keys (4 kg + i) x query column r16, folded into (m, l);
-  // `vis[qt]`: keys with index below it are visible to this lane's query column of tile qt
-  auto fold = [&](const bf16x8 (&kf)[KS], int key0, const int (&vis)[kSbTiles], bool masked) {
-#pragma unroll
-    for (int qt = 0; qt < kSbTiles; ++qt) {
-      f32x4 acc = {0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-      for (int ks = 0; ks < KS; ++ks) acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kf[ks], qf[qt][ks], acc, 0, 0, 0);
-      float x[4];
-#pragma unroll
-      for (int i = 0; i < 4; ++i) {
-        x[i] = acc[i] * p.scale_log2;
-        if (masked && key0 + 4 * kg + i >= vis[qt]) x[i] = -INFINITY;
-      }
-      const float mx = fmaxf(fmaxf(x[0], x[1]), fmaxf(x[2], x[3]));
-      const float mn = fmaxf(m[qt], mx);
-      float s = l[qt] * fast_exp2(m[qt] - mn);
-#pragma unroll
-      for (int i = 0; i < 4; ++i) s += fast_exp2(x[i] - mn);
-      m[qt] = mn;
-      l[qt] = s;
-    }
-  };
-
-  // cached slots: full tiles unmasked, then the ragged tail
-  {
-    int vis[kSbTiles];
-#pragma unroll
-    for (int qt = 0; qt < kSbTiles; ++qt) vis[qt] = n;
-    bf16x8 kf[KS], kn[KS];
-    const int n_full = n & ~15;
-    if (n > 0) {
-      int row = r16 < n ? r16 : n - 1;
-      load_row_frags<D>(kf, Kb + (size_t)row * D, kg);
-    }
-    for (int j0 = 0; j0 < n_full; j0 += 16) {
-      int row = j0 + 16 + r16;
-      row = row < n ? row : n - 1;
-      load_row_frags<D>(kn, Kb + (size_t)row * D, kg);
-      fold(kf, j0, vis, false);
-#pragma unroll
-      for (int ks = 0; ks < KS; ++ks) kf[ks] = kn[ks];
-    }
-    if (n_full < n) fold(kf, n_full, vis, true);
+  // one streamed tile: keys (4 kg + i) x query column r16, folded into (m, l).  MASKED: keys whose
+  // index key0 + 4 kg + i is not below lim[qt] do not exist for this query column.
+#define DYNTS_SB_FOLD(kf_, MASKED, key0_, lim_)                                                        \
+  _Pragma("unroll") for (int qt = 0; qt < kSbTiles; ++qt) {                                            \
+    f32x4 acc = {0.f, 0.f, 0.f, 0.f};                                                                  \
+    _Pragma("unroll") for (int ks = 0; ks < KS; ++ks)                                                  \
+        acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kf_[ks], qf[qt][ks], acc, 0, 0, 0);              \
+    if (MASKED) {                                                                                      \
+      _Pragma("unroll") for (int i = 0; i < 4; ++i)                                                    \
+          if ((key0_) + 4 * kg + i >= lim_[qt]) acc[i] = -INFINITY;                                    \
+    }                                                                                                  \
+    const float mn = fmaxf(fmaxf(fmaxf(acc[0], acc[1]), fmaxf(acc[2], acc[3])), m[qt]);                \
+    const float nm = -mn * c;                                                                          \
+    float sum = l[qt] * fast_exp2((m[qt] - mn) * c); /* exactly 2^0 while nothing has been seen */     \
+    _Pragma("unroll") for (int i = 0; i < 4; ++i) sum += fast_exp2(fmaf(acc[i], c, nm));               \
+    m[qt] = mn;                                                                                        \
+    l[qt] = sum;                                                                                       \
   }
 
-  // the block's own keys, causally: key i' is visible to query row r iff i' <= r / G
+  // cached slots: pairs of full tiles from two register buffers in turn, then the ragged rest
+  {
+    int lim[kSbTiles];
+#pragma unroll
+    for (int qt = 0; qt < kSbTiles; ++qt) lim[qt] = n;
+    bf16x8 ka[KS], kb[KS];
+    const int n_pairs = n & ~31;
+    const uint32_t last_off = (uint32_t)(n > 0 ? n - 1 : 0) * (uint32_t)(2 * D);
+    uint32_t off = (uint32_t)r16 * (uint32_t)(2 * D);
+    if (n > 0) load_row_frags<D>(ka, Kb + (off < last_off ? off : last_off), kg);
+    for (int j0 = 0; j0 < n_pairs; j0 += 32) {
+      load_row_frags<D>(kb, Kb + off + 16 * 2 * D, kg);  // tile j0 + 16 is full: j0 + 32 <= n
+      DYNTS_SB_FOLD(ka, false, 0, lim)
+      off += 32 * 2 * D;
+      load_row_frags<D>(ka, Kb + (off < last_off ? off : last_off), kg);
+      DYNTS_SB_FOLD(kb, false, 0, lim)
+    }
+    if (n_pairs < n) {
+      DYNTS_SB_FOLD(ka, true, n_pairs, lim)
+      if (n_pairs + 16 < n) {
+        const uint32_t o2 = off + 16 * 2 * D;
+        load_row_frags<D>(kb, Kb + (o2 < last_off ? o2 : last_off), kg);
+        DYNTS_SB_FOLD(kb, true, n_pairs + 16, lim)
+      }
+    }
+  }
+
+  // the block's own keys, causally: key i' is visible to query row (i, g) iff i' <= i
   if (p.k_blk) {
-    int vis[kSbTiles];
     int last = row0 + kSbRowsPerWave - 1;
     last = last < R ? last : R - 1;
     const int i_hi = last / p.G + 1;  // keys [0, i_hi) are visible to some row of this wave
-#pragma unroll
-    for (int qt = 0; qt < kSbTiles; ++qt) {
-      int r = row0 + 16 * qt + r16;
-      r = r < R ? r : R - 1;
-      vis[qt] = r / p.G + 1;
-    }
-    const uint16_t *kb0 = p.k_blk + ((size_t)b * p.T * p.Hkv + h) * D;
-    const size_t kstride = (size_t)p.Hkv * D;
+    const char *kb0 = reinterpret_cast<const char *>(p.k_blk + ((size_t)b * p.T * p.Hkv + h) * D);
+    const size_t kstride = (size_t)p.Hkv * D * 2;
+    bf16x8 kf[KS], kn[KS];
+    load_row_frags<D>(kf, kb0 + (size_t)(r16 < p.T ? r16 : p.T - 1) * kstride, kg);
     for (int i0 = 0; i0 < i_hi; i0 += 16) {
-      bf16x8 kf[KS];
-      int row = i0 + r16;
+      int row = i0 + 16 + r16;
       row = row < p.T ? row : p.T - 1;
-      load_row_frags<D>(kf, kb0 + (size_t)row * kstride, kg);
-      fold(kf, i0, vis, true);
+      load_row_frags<D>(kn, kb0 + (size_t)row * kstride, kg);
+      DYNTS_SB_FOLD(kf, true, i0, vis_blk)
+#pragma unroll
+      for (int ks = 0; ks < KS; ++ks) kf[ks] = kn[ks];
     }
   }
+#undef DYNTS_SB_FOLD
 
-  // merge the four lane groups of every query column, write L = m + log2(l)
+  // merge the four lane groups of every query column, write L = c * m + log2(l)
 #pragma unroll
   for (int qt = 0; qt < kSbTiles; ++qt) {
 #pragma unroll
     for (int sh = 16; sh <= 32; sh <<= 1) {
       const float mo = __shfl_xor(m[qt], sh), lo = __shfl_xor(l[qt], sh);
       const float mn = fmaxf(m[qt], mo);
-      l[qt] = l[qt] * fast_exp2(m[qt] - mn) + lo * fast_exp2(mo - mn);
+      l[qt] = l[qt] * fast_exp2((m[qt] - mn) * c) + lo * fast_exp2((mo - mn) * c);
       m[qt] = mn;
     }
     const int r = row0 + 16 * qt + r16;
-    if (kg == 0 && r < R) p.stats[unit * (size_t)p.Rpad + r] = m[qt] + __builtin_amdgcn_logf(l[qt]);
+    if (kg == 0 && r < R) p.stats[(size_t)unit * (size_t)p.Rpad + r] = m[qt] * c + __builtin_amdgcn_logf(l[qt]);
   }
 }
 
 // ---- pass 2: attention received by every cached slot, summed over the block's query rows ----------
-// grid (ceil(cap / 256), Hkv, Nb), 256 threads.
+// 1-D grid of ceil(cap / 256) * round_up(units, 8) workgroups, 256 threads.
 template <int D>
 __global__ __launch_bounds__(kSbWaves * 64) void score_block_colsum_kernel(const ScoreBlockParams p) {
   constexpr int KS = D / 32;
-  const int b = blockIdx.z, h = blockIdx.y;
+  int unit, blk;
+  if (!sb_map((p.cap + kSbRowsPerWg - 1) / kSbRowsPerWg, p.Nb * p.Hkv, unit, blk)) return;
+  const int b = unit / p.Hkv, h = unit - b * p.Hkv;
   if (p.active && !p.active[b]) return;
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int r16 = lane & 15, kg = lane >> 4;
@@ -196,11 +237,12 @@ __global__ __launch_bounds__(kSbWaves * 64) void score_block_colsum_kernel(const
     first = p.n_prompt[b];
     first = first < 0 ? 0 : first;
   }
-  const int key0 = blockIdx.x * kSbRowsPerWg + wave * kSbRowsPerWave;
+  const int key0 = blk * kSbRowsPerWg + wave * kSbRowsPerWave;
   if (key0 >= n || key0 + kSbRowsPerWave <= first) return;
-  const size_t unit = (size_t)b * p.Hkv + h;
-  const uint16_t *Kb = p.K + unit * (size_t)p.cap * D;
-  const float *Lb = p.stats + unit * (size_t)p.Rpad;
+  const char *Kb = reinterpret_cast<const char *>(p.K + (size_t)unit * (size_t)p.cap * D);
+  const char *Qb = reinterpret_cast<const char *>(p.q_blk + ((size_t)b * p.T * p.Hq + (size_t)h * p.G) * D);
+  const float *Lb = p.stats + (size_t)unit * (size_t)p.Rpad;
+  const float c = p.scale_log2;
 
   // stationary: this wave's cached keys (A operand: row r16 of tile kt is slot key0 + 16 kt + r16)
   bf16x8 kf[kSbTiles][KS];
@@ -208,32 +250,39 @@ __global__ __launch_bounds__(kSbWaves * 64) void score_block_colsum_kernel(const
   for (int kt = 0; kt < kSbTiles; ++kt) {
     int row = key0 + 16 * kt + r16;
     row = row < n ? row : n - 1;
-    load_row_frags<D>(kf[kt], Kb + (size_t)row * D, kg);
+    load_row_frags<D>(kf[kt], Kb + (size_t)row * (size_t)(2 * D), kg);
   }
   f32x4 sum[kSbTiles];
 #pragma unroll
   for (int kt = 0; kt < kSbTiles; ++kt) sum[kt] = f32x4{0.f, 0.f, 0.f, 0.f};
 
-  bf16x8 qf[KS], qn[KS];
-  float L, Ln;
-  load_row_frags<D>(qf, query_row<D>(p, b, h, r16, R), kg);
-  L = r16 < R ? Lb[r16] : INFINITY;
-  for (int r0 = 0; r0 < R; r0 += 16) {
-    const int rn = r0 + 16 + r16;
-    load_row_frags<D>(qn, query_row<D>(p, b, h, rn, R), kg);
-    Ln = rn < R ? Lb[rn] : INFINITY;   // a row beyond the last contributes 2^(-inf) = 0
-#pragma unroll
-    for (int kt = 0; kt < kSbTiles; ++kt) {
-      f32x4 acc = {0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-      for (int ks = 0; ks < KS; ++ks) acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kf[kt][ks], qf[ks], acc, 0, 0, 0);
-#pragma unroll
-      for (int i = 0; i < 4; ++i) sum[kt][i] += fast_exp2(acc[i] * p.scale_log2 - L);
-    }
-#pragma unroll
-    for (int ks = 0; ks < KS; ++ks) qf[ks] = qn[ks];
-    L = Ln;
+  // streamed: 16 query rows at a time from two register buffers in turn.  A row beyond the last
+  // repeats the last row's data with L = +inf, so it contributes 2^(-inf) = 0.
+  QueryWalk w;
+  w.init(r16, p.G, p.Hq, D);
+  const uint32_t last_off = (uint32_t)(p.T - 1) * w.stride_i + (uint32_t)(p.G - 1) * w.stride_g;
+#define DYNTS_SB_LOAD(qf_, L_)                                           \
+  load_row_frags<D>(qf_, Qb + (w.r < R ? w.off : last_off), kg);        \
+  L_ = w.r < R ? Lb[w.r] : INFINITY;                                     \
+  w.advance(p.G);
+#define DYNTS_SB_ADD(qf_, L_)                                                                          \
+  _Pragma("unroll") for (int kt = 0; kt < kSbTiles; ++kt) {                                            \
+    f32x4 acc = {0.f, 0.f, 0.f, 0.f};                                                                  \
+    _Pragma("unroll") for (int ks = 0; ks < KS; ++ks)                                                  \
+        acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kf[kt][ks], qf_[ks], acc, 0, 0, 0);              \
+    _Pragma("unroll") for (int i = 0; i < 4; ++i) sum[kt][i] += fast_exp2(fmaf(acc[i], c, -L_));       \
   }
+  bf16x8 qa[KS], qb[KS];
+  float La, Lq;
+  DYNTS_SB_LOAD(qa, La)
+  for (int r0 = 0; r0 < R; r0 += 32) {
+    DYNTS_SB_LOAD(qb, Lq)
+    DYNTS_SB_ADD(qa, La)
+    DYNTS_SB_LOAD(qa, La)
+    DYNTS_SB_ADD(qb, Lq)
+  }
+#undef DYNTS_SB_LOAD
+#undef DYNTS_SB_ADD
 
   // sum[kt][i] holds slot key0 + 16 kt + 4 kg + i for query columns == r16 (mod 16): add the 16 lanes
 #pragma unroll
@@ -258,7 +307,7 @@ __global__ __launch_bounds__(kSbWaves * 64) void score_block_colsum_kernel(const
       if (kt == kt_w && i == i_w) v = sum[kt][i];
   const int slot = key0 + 16 * kt_w + 4 * kg + i_w;
   if (slot < n && slot >= first) {
-    float *d = p.dst + unit * (size_t)p.cap + slot;
+    float *d = p.dst + (size_t)unit * (size_t)p.cap + slot;
     *d = p.accumulate ? *d + v : v;
   }
 }
