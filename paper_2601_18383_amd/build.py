@@ -10,6 +10,7 @@ HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
          "-mllvm", "-amdgpu-mfma-vgpr-form",   # MFMA results straight into arch VGPRs (no AGPR copies)
+         "-Xarch_device", "-fno-honor-nans",   # device code only: no canonicalising v_max before every fmaxf
          "-Wall", "-Wno-unused-function"]
 
 

@@ -10,17 +10,20 @@
 // (row, slot) of HBM traffic each way, which at these shapes is several times slower.
 //
 // Both passes have the same shape.  A wave keeps 64 rows of one operand in registers (pass 1: query
-// rows, pass 2: cached keys) and streams the other operand through in 16-row tiles straight from
-// global memory into MFMA operand registers (lane (r, kg) holds elements 32*ks + 8*kg .. +7 of row
-// r, the layout v_mfma_f32_16x16x32_bf16 wants for A and for B alike), next tile's loads in flight
-// while the current one is multiplied.  The product is always  keys (A, rows)  x  queries (B,
-// columns): a lane ends up with 4 keys of ONE query column, so
+// rows, pass 2: cached keys) as MFMA operand fragments (lane (r, kg) holds elements
+// 32*ks + 8*kg .. +7 of row r, the layout v_mfma_f32_16x16x32_bf16 wants for A and for B alike).
+// The other operand is streamed: the workgroup's 256 threads fetch 32 rows at a time with whole-row
+// coalesced 16-byte loads (a strided fetch straight into operand layout touches 16 cache lines per
+// instruction and makes the L1 tag rate the limit), park them in one of two padded LDS buffers, and
+// every wave reads its operand fragments back from there (row pitch +16 bytes: the 16 rows a
+// ds_read_b128 touches fall into different banks).  Loads for chunk c+2 are in flight while chunk
+// c is multiplied; one barrier per chunk.
+// The product is always  keys (A, rows)  x  queries (B, columns): a lane ends up with 4 keys of ONE
+// query column, so
 //   * pass 1 keeps a private running (max, sum) per lane and query column and merges the four lane
 //     groups once, at the end;
 //   * pass 2 keeps private partial column sums per lane and key and merges the 16 lanes of a group
 //     once, at the end.
-// The four waves of a workgroup hold different stationary rows and stream the same tiles, which
-// therefore come from L1/L2 after the first wave has touched them.  No LDS, no barrier.
 #pragma once
 #include <hip/hip_runtime.h>
 #include <stdint.h>
@@ -49,10 +52,32 @@ struct ScoreBlockParams {
   float scale_log2;         // softmax scale * log2(e)
 };
 
-// MFMA operand fragments of one row: 16 bytes per k-step at the lane's column group.
+// MFMA operand fragments of one row in global memory: 16 bytes per k-step at the lane's column group.
 template <int D>
 __device__ __forceinline__ void load_row_frags(bf16x8 (&f)[D / 32], const char *row, int kg) {
   const char *base = row + 16 * kg;
+#pragma unroll
+  for (int ks = 0; ks < D / 32; ++ks)
+    f[ks] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const u32x4 *>(base + 64 * ks));
+}
+
+// Staging of the streamed operand: a chunk is 32 rows; thread t of the 256 fetches 16 bytes of row
+// t / PIECES (+ RPP per further load) at piece t % PIECES, so 16 (8) neighbouring lanes read one
+// whole row.
+template <int D>
+struct SbStage {
+  static constexpr int kChunk = 32;              // rows per chunk
+  static constexpr int PIECES = D / 8;           // 16-byte pieces per row
+  static constexpr int RPP = 256 / PIECES;       // rows one load instruction of the workgroup covers
+  static constexpr int NL = kChunk / RPP;        // load instructions per chunk and thread
+  static constexpr int LROW = 2 * D + 16;        // padded row pitch in LDS, bytes
+  static constexpr int kBufBytes = kChunk * LROW;
+};
+
+// operand fragments of row `row` (0..31) of a staged chunk
+template <int D>
+__device__ __forceinline__ void lds_row_frags(bf16x8 (&f)[D / 32], const char *buf, int row, int kg) {
+  const char *base = buf + row * SbStage<D>::LROW + 16 * kg;
 #pragma unroll
   for (int ks = 0; ks < D / 32; ++ks)
     f[ks] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const u32x4 *>(base + 64 * ks));
@@ -68,24 +93,25 @@ __device__ __forceinline__ bool sb_map(int n_blk, int n_units, int &unit, int &b
   return unit < n_units;
 }
 
-// A lane's walk over the query rows r = i * G + g of a KV head's group, 16 rows at a time.
+// A thread's walk over the query rows r = i * G + g of a KV head's group, `step` rows at a time.
 struct QueryWalk {
-  int r, i, g;
+  int r, i, g, step;
   uint32_t off;         // byte offset of row (i, g) from the (sequence, head-group) base
-  int step_i, step_g;   // 16 = step_i * G + step_g
+  int step_i, step_g;   // step = step_i * G + step_g
   uint32_t stride_i, stride_g;
-  __device__ __forceinline__ void init(int r0, int G, int Hq, int D) {
+  __device__ __forceinline__ void init(int r0, int step_, int G, int Hq, int D) {
     r = r0;
+    step = step_;
     i = r0 / G;
     g = r0 - i * G;
-    step_i = 16 / G;
-    step_g = 16 - step_i * G;
+    step_i = step / G;
+    step_g = step - step_i * G;
     stride_i = (uint32_t)Hq * D * 2;
     stride_g = (uint32_t)D * 2;
     off = (uint32_t)i * stride_i + (uint32_t)g * stride_g;
   }
   __device__ __forceinline__ void advance(int G) {
-    r += 16;
+    r += step;
     i += step_i;
     g += step_g;
     off += (uint32_t)step_i * stride_i + (uint32_t)step_g * stride_g;
@@ -102,15 +128,18 @@ struct QueryWalk {
 template <int D>
 __global__ __launch_bounds__(kSbWaves * 64) void score_block_stats_kernel(const ScoreBlockParams p) {
   constexpr int KS = D / 32;
+  using St = SbStage<D>;
+  __shared__ __attribute__((aligned(16))) char lds[2][St::kBufBytes];
   const int R = p.T * p.G;
   int unit, blk;
   if (!sb_map((R + kSbRowsPerWg - 1) / kSbRowsPerWg, p.Nb * p.Hkv, unit, blk)) return;
   const int b = unit / p.Hkv, h = unit - b * p.Hkv;
   if (p.active && !p.active[b]) return;
-  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  if (blk * kSbRowsPerWg >= R) return;  // (cannot happen with the grid above; uniform over the workgroup)
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int r16 = lane & 15, kg = lane >> 4;
   const int row0 = blk * kSbRowsPerWg + wave * kSbRowsPerWave;
-  if (row0 >= R) return;
+  const bool has_rows = row0 < R;  // a wave without rows still helps staging and meets the barriers
   int n = p.seq_len[b];
   n = n < 0 ? 0 : (n > p.cap ? p.cap : n);
   const char *Kb = reinterpret_cast<const char *>(p.K + (size_t)unit * (size_t)p.cap * D);
@@ -130,10 +159,11 @@ __global__ __launch_bounds__(kSbWaves * 64) void score_block_stats_kernel(const 
   }
 
   // running max (in raw dot-product units) and sum of 2^(c * (dot - max)), private to the lane
-  float m[kSbTiles], l[kSbTiles];
+  float m[kSbTiles], nm[kSbTiles], l[kSbTiles];  // nm = -c * m, the exponent's addend
 #pragma unroll
   for (int qt = 0; qt < kSbTiles; ++qt) {
     m[qt] = -1e30f;
+    nm[qt] = 1e30f * c;
     l[qt] = 0.f;
   }
 
@@ -148,60 +178,84 @@ __global__ __launch_bounds__(kSbWaves * 64) void score_block_stats_kernel(const 
       _Pragma("unroll") for (int i = 0; i < 4; ++i)                                                    \
           if ((key0_) + 4 * kg + i >= lim_[qt]) acc[i] = -INFINITY;                                    \
     }                                                                                                  \
-    const float mn = fmaxf(fmaxf(fmaxf(acc[0], acc[1]), fmaxf(acc[2], acc[3])), m[qt]);                \
-    const float nm = -mn * c;                                                                          \
-    float sum = l[qt] * fast_exp2((m[qt] - mn) * c); /* exactly 2^0 while nothing has been seen */     \
-    _Pragma("unroll") for (int i = 0; i < 4; ++i) sum += fast_exp2(fmaf(acc[i], c, nm));               \
-    m[qt] = mn;                                                                                        \
+    const float mx = fmaxf(fmaxf(acc[0], acc[1]), fmaxf(acc[2], acc[3]));                              \
+    if (__any(mx > m[qt])) { /* some lane's maximum rises (rare after the first tiles): rescale */     \
+      const float mn = fmaxf(mx, m[qt]);                                                               \
+      l[qt] *= fast_exp2((m[qt] - mn) * c); /* exactly 2^0 where nothing changes */                    \
+      m[qt] = mn;                                                                                      \
+      nm[qt] = -mn * c;                                                                                \
+    }                                                                                                  \
+    float sum = l[qt];                                                                                 \
+    _Pragma("unroll") for (int i = 0; i < 4; ++i) sum += fast_exp2(fmaf(acc[i], c, nm[qt]));           \
     l[qt] = sum;                                                                                       \
   }
 
-  // cached slots: pairs of full tiles from two register buffers in turn, then the ragged rest
+  // Streaming of `rows` rows that start at `src` with pitch `pitch` bytes, 32 per chunk; row indices
+  // beyond the last repeat it (the fold masks them).  Every thread of the workgroup runs this.
+  const int st_row = tid / St::PIECES, st_piece = tid % St::PIECES;
+  u32x4 stage[St::NL];
+#define DYNTS_SB_FETCH(src_, pitch_, rows_, chunk_)                                                    \
+  _Pragma("unroll") for (int k = 0; k < St::NL; ++k) {                                                 \
+    int row = (chunk_) * St::kChunk + st_row + St::RPP * k;                                            \
+    row = row < (rows_) ? row : (rows_) - 1;                                                           \
+    stage[k] = *reinterpret_cast<const u32x4 *>((src_) + (size_t)row * (pitch_) + 16 * st_piece);      \
+  }
+#define DYNTS_SB_PARK(buf_)                                                                            \
+  _Pragma("unroll") for (int k = 0; k < St::NL; ++k)                                                   \
+      *reinterpret_cast<u32x4 *>((buf_) + (st_row + St::RPP * k) * St::LROW + 16 * st_piece) = stage[k];
+#define DYNTS_SB_STREAM(src_, pitch_, rows_, lim_, CAUSAL_)                                                    \
+  {                                                                                                    \
+    const int n_chunks = ((rows_) + St::kChunk - 1) / St::kChunk;                                      \
+    if (n_chunks > 0) {                                                                                \
+      DYNTS_SB_FETCH(src_, pitch_, rows_, 0)                                                           \
+      DYNTS_SB_PARK(lds[0])                                                                            \
+      if (n_chunks > 1) { DYNTS_SB_FETCH(src_, pitch_, rows_, 1) }                                     \
+      __syncthreads();                                                                                 \
+      for (int ch = 0; ch < n_chunks; ++ch) {                                                          \
+        const char *buf = lds[ch & 1];                                                                 \
+        if (has_rows) {                                                                                \
+          if ((CAUSAL_) || (ch + 1) * St::kChunk > (rows_)) { /* uniform: some keys are masked */      \
+            _Pragma("unroll") for (int tt = 0; tt < 2; ++tt) {                                         \
+              bf16x8 kf[KS];                                                                           \
+              lds_row_frags<D>(kf, buf, 16 * tt + r16, kg);                                            \
+              DYNTS_SB_FOLD(kf, true, ch * St::kChunk + 16 * tt, lim_)                                 \
+            }                                                                                          \
+          } else {                                                                                     \
+            _Pragma("unroll") for (int tt = 0; tt < 2; ++tt) {                                         \
+              bf16x8 kf[KS];                                                                           \
+              lds_row_frags<D>(kf, buf, 16 * tt + r16, kg);                                            \
+              DYNTS_SB_FOLD(kf, false, 0, lim_)                                                        \
+            }                                                                                          \
+          }                                                                                            \
+        }                                                                                              \
+        if (ch + 1 < n_chunks) { DYNTS_SB_PARK(lds[(ch + 1) & 1]) }                                    \
+        if (ch + 2 < n_chunks) { DYNTS_SB_FETCH(src_, pitch_, rows_, ch + 2) }                         \
+        __syncthreads();                                                                               \
+      }                                                                                                \
+    }                                                                                                  \
+  }
+
+  // cached slots: every query column sees all n of them
   {
     int lim[kSbTiles];
 #pragma unroll
     for (int qt = 0; qt < kSbTiles; ++qt) lim[qt] = n;
-    bf16x8 ka[KS], kb[KS];
-    const int n_pairs = n & ~31;
-    const uint32_t last_off = (uint32_t)(n > 0 ? n - 1 : 0) * (uint32_t)(2 * D);
-    uint32_t off = (uint32_t)r16 * (uint32_t)(2 * D);
-    if (n > 0) load_row_frags<D>(ka, Kb + (off < last_off ? off : last_off), kg);
-    for (int j0 = 0; j0 < n_pairs; j0 += 32) {
-      load_row_frags<D>(kb, Kb + off + 16 * 2 * D, kg);  // tile j0 + 16 is full: j0 + 32 <= n
-      DYNTS_SB_FOLD(ka, false, 0, lim)
-      off += 32 * 2 * D;
-      load_row_frags<D>(ka, Kb + (off < last_off ? off : last_off), kg);
-      DYNTS_SB_FOLD(kb, false, 0, lim)
-    }
-    if (n_pairs < n) {
-      DYNTS_SB_FOLD(ka, true, n_pairs, lim)
-      if (n_pairs + 16 < n) {
-        const uint32_t o2 = off + 16 * 2 * D;
-        load_row_frags<D>(kb, Kb + (o2 < last_off ? o2 : last_off), kg);
-        DYNTS_SB_FOLD(kb, true, n_pairs + 16, lim)
-      }
-    }
+    DYNTS_SB_STREAM(Kb, (size_t)(2 * D), n, lim, false)
   }
-
-  // the block's own keys, causally: key i' is visible to query row (i, g) iff i' <= i
+  // the block's own keys, causally: key i' is visible to query row (i, g) iff i' <= i.  Keys
+  // [0, i_hi) are visible to some row of this workgroup.
   if (p.k_blk) {
-    int last = row0 + kSbRowsPerWave - 1;
+    int last = blk * kSbRowsPerWg + kSbRowsPerWg - 1;
     last = last < R ? last : R - 1;
-    const int i_hi = last / p.G + 1;  // keys [0, i_hi) are visible to some row of this wave
+    const int i_hi = last / p.G + 1;
     const char *kb0 = reinterpret_cast<const char *>(p.k_blk + ((size_t)b * p.T * p.Hkv + h) * D);
-    const size_t kstride = (size_t)p.Hkv * D * 2;
-    bf16x8 kf[KS], kn[KS];
-    load_row_frags<D>(kf, kb0 + (size_t)(r16 < p.T ? r16 : p.T - 1) * kstride, kg);
-    for (int i0 = 0; i0 < i_hi; i0 += 16) {
-      int row = i0 + 16 + r16;
-      row = row < p.T ? row : p.T - 1;
-      load_row_frags<D>(kn, kb0 + (size_t)row * kstride, kg);
-      DYNTS_SB_FOLD(kf, true, i0, vis_blk)
-#pragma unroll
-      for (int ks = 0; ks < KS; ++ks) kf[ks] = kn[ks];
-    }
+    DYNTS_SB_STREAM(kb0, (size_t)p.Hkv * D * 2, i_hi, vis_blk, true)
   }
+#undef DYNTS_SB_STREAM
+#undef DYNTS_SB_PARK
+#undef DYNTS_SB_FETCH
 #undef DYNTS_SB_FOLD
+  if (!has_rows) return;
 
   // merge the four lane groups of every query column, write L = c * m + log2(l)
 #pragma unroll
@@ -223,11 +277,13 @@ __global__ __launch_bounds__(kSbWaves * 64) void score_block_stats_kernel(const 
 template <int D>
 __global__ __launch_bounds__(kSbWaves * 64) void score_block_colsum_kernel(const ScoreBlockParams p) {
   constexpr int KS = D / 32;
+  using St = SbStage<D>;
+  __shared__ __attribute__((aligned(16))) char lds[2][St::kBufBytes];
   int unit, blk;
   if (!sb_map((p.cap + kSbRowsPerWg - 1) / kSbRowsPerWg, p.Nb * p.Hkv, unit, blk)) return;
   const int b = unit / p.Hkv, h = unit - b * p.Hkv;
   if (p.active && !p.active[b]) return;
-  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int r16 = lane & 15, kg = lane >> 4;
   const int R = p.T * p.G;
   int n = p.seq_len[b];
@@ -237,8 +293,10 @@ __global__ __launch_bounds__(kSbWaves * 64) void score_block_colsum_kernel(const
     first = p.n_prompt[b];
     first = first < 0 ? 0 : first;
   }
+  // uniform over the workgroup: nothing of this block is wanted
+  if (blk * kSbRowsPerWg >= n || (blk + 1) * kSbRowsPerWg <= first) return;
   const int key0 = blk * kSbRowsPerWg + wave * kSbRowsPerWave;
-  if (key0 >= n || key0 + kSbRowsPerWave <= first) return;
+  const bool has_keys = key0 < n && key0 + kSbRowsPerWave > first;  // else: staging and barriers only
   const char *Kb = reinterpret_cast<const char *>(p.K + (size_t)unit * (size_t)p.cap * D);
   const char *Qb = reinterpret_cast<const char *>(p.q_blk + ((size_t)b * p.T * p.Hq + (size_t)h * p.G) * D);
   const float *Lb = p.stats + (size_t)unit * (size_t)p.Rpad;
@@ -256,33 +314,76 @@ __global__ __launch_bounds__(kSbWaves * 64) void score_block_colsum_kernel(const
 #pragma unroll
   for (int kt = 0; kt < kSbTiles; ++kt) sum[kt] = f32x4{0.f, 0.f, 0.f, 0.f};
 
-  // streamed: 16 query rows at a time from two register buffers in turn.  A row beyond the last
-  // repeats the last row's data with L = +inf, so it contributes 2^(-inf) = 0.
-  QueryWalk w;
-  w.init(r16, p.G, p.Hq, D);
-  const uint32_t last_off = (uint32_t)(p.T - 1) * w.stride_i + (uint32_t)(p.G - 1) * w.stride_g;
-#define DYNTS_SB_LOAD(qf_, L_)                                           \
-  load_row_frags<D>(qf_, Qb + (w.r < R ? w.off : last_off), kg);        \
-  L_ = w.r < R ? Lb[w.r] : INFINITY;                                     \
-  w.advance(p.G);
-#define DYNTS_SB_ADD(qf_, L_)                                                                          \
-  _Pragma("unroll") for (int kt = 0; kt < kSbTiles; ++kt) {                                            \
-    f32x4 acc = {0.f, 0.f, 0.f, 0.f};                                                                  \
+  // streamed: the R query rows, 32 per chunk through LDS.  A row beyond the last repeats the last
+  // row's data and gets L = +inf, so it contributes 2^(-inf) = 0.
+  const int st_piece = tid % St::PIECES;
+  QueryWalk w[St::NL];
+#pragma unroll
+  for (int k = 0; k < St::NL; ++k) w[k].init(tid / St::PIECES + St::RPP * k, St::kChunk, p.G, p.Hq, D);
+  const uint32_t last_off = (uint32_t)(p.T - 1) * w[0].stride_i + (uint32_t)(p.G - 1) * w[0].stride_g;
+  u32x4 stage[St::NL];
+#define DYNTS_SB_FETCH()                                                                               \
+  _Pragma("unroll") for (int k = 0; k < St::NL; ++k) {                                                 \
+    stage[k] = *reinterpret_cast<const u32x4 *>(Qb + (w[k].r < R ? w[k].off : last_off) + 16 * st_piece); \
+    w[k].advance(p.G);                                                                                 \
+  }
+#define DYNTS_SB_PARK(buf_)                                                                            \
+  _Pragma("unroll") for (int k = 0; k < St::NL; ++k)                                                   \
+      *reinterpret_cast<u32x4 *>((buf_) + (tid / St::PIECES + St::RPP * k) * St::LROW + 16 * st_piece) = stage[k];
+
+  // The tiles are software-pipelined: the MFMAs of tile t+1 (independent accumulators, so they issue
+  // back to back) stand next to the exponentials and sums of tile t, so that the scheduler has
+  // independent work for the matrix pipe and the vector ALU at the same time.
+#define DYNTS_SB_MM(acc_, buf_, tt_)                                                                   \
+  {                                                                                                    \
+    bf16x8 qf[KS];                                                                                     \
+    lds_row_frags<D>(qf, buf_, 16 * (tt_) + r16, kg);                                                  \
+    _Pragma("unroll") for (int kt = 0; kt < kSbTiles; ++kt) acc_[kt] = f32x4{0.f, 0.f, 0.f, 0.f};      \
     _Pragma("unroll") for (int ks = 0; ks < KS; ++ks)                                                  \
-        acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kf[kt][ks], qf_[ks], acc, 0, 0, 0);              \
-    _Pragma("unroll") for (int i = 0; i < 4; ++i) sum[kt][i] += fast_exp2(fmaf(acc[i], c, -L_));       \
+      _Pragma("unroll") for (int kt = 0; kt < kSbTiles; ++kt)                                          \
+          acc_[kt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kf[kt][ks], qf[ks], acc_[kt], 0, 0, 0);   \
   }
-  bf16x8 qa[KS], qb[KS];
-  float La, Lq;
-  DYNTS_SB_LOAD(qa, La)
-  for (int r0 = 0; r0 < R; r0 += 32) {
-    DYNTS_SB_LOAD(qb, Lq)
-    DYNTS_SB_ADD(qa, La)
-    DYNTS_SB_LOAD(qa, La)
-    DYNTS_SB_ADD(qb, Lq)
+#define DYNTS_SB_SUM(acc_, L_)                                                                         \
+  _Pragma("unroll") for (int kt = 0; kt < kSbTiles; ++kt)                                              \
+    _Pragma("unroll") for (int i = 0; i < 4; ++i) sum[kt][i] += fast_exp2(fmaf(acc_[kt][i], c, -(L_)));
+
+  const int n_chunks = (R + St::kChunk - 1) / St::kChunk;
+  DYNTS_SB_FETCH()
+  DYNTS_SB_PARK(lds[0])
+  if (n_chunks > 1) { DYNTS_SB_FETCH() }
+  float La = r16 < R ? Lb[r16] : INFINITY;  // log2 denominator of this lane's query column, even tile
+  float Lq = 16 + r16 < R ? Lb[16 + r16] : INFINITY;  // ... odd tile of the chunk
+  f32x4 acc_a[kSbTiles], acc_b[kSbTiles];
+  __syncthreads();
+  if (has_keys) DYNTS_SB_MM(acc_a, lds[0], 0)
+  for (int ch = 0; ch < n_chunks; ++ch) {
+    const char *buf = lds[ch & 1];
+    const int rn = (ch + 1) * St::kChunk + r16;
+    const float La_n = rn < R ? Lb[rn] : INFINITY;
+    const float Lq_n = rn + 16 < R ? Lb[rn + 16] : INFINITY;
+    if (has_keys) {
+      DYNTS_SB_MM(acc_b, buf, 1)
+      DYNTS_SB_SUM(acc_a, La)
+    }
+    if (ch + 1 < n_chunks) { DYNTS_SB_PARK(lds[(ch + 1) & 1]) }
+    if (ch + 2 < n_chunks) { DYNTS_SB_FETCH() }
+    __syncthreads();
+    if (has_keys) {
+      if (ch + 1 < n_chunks) {
+        DYNTS_SB_MM(acc_a, lds[(ch + 1) & 1], 0)
+        DYNTS_SB_SUM(acc_b, Lq)
+      } else {
+        DYNTS_SB_SUM(acc_b, Lq)
+      }
+    }
+    La = La_n;
+    Lq = Lq_n;
   }
-#undef DYNTS_SB_LOAD
-#undef DYNTS_SB_ADD
+#undef DYNTS_SB_MM
+#undef DYNTS_SB_SUM
+#undef DYNTS_SB_FETCH
+#undef DYNTS_SB_PARK
+  if (!has_keys) return;
 
   // sum[kt][i] holds slot key0 + 16 kt + 4 kg + i for query columns == r16 (mod 16): add the 16 lanes
 #pragma unroll
