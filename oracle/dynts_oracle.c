@@ -217,6 +217,48 @@ int dynts_oracle_score_block(int Nb, int T, int Hq, int Hkv, int d, int cap,
   return bad ? -1 : 0;
 }
 
+/*
+ * Importance Predictor (Sec. 4.1; App. A "Predictor Overhead"; App. C gives the sizes
+ * 3584->7168->1792->1 and 4096->8192->2048->1): a three-layer MLP d -> m1 -> m2 -> 1 on the final
+ * hidden state of the current token, one score per token.
+ *   h  [Nb][d]     W1 [m1][d], b1 [m1]     W2 [m2][m1], b2 [m2]     w3 [m2], b3 [1]   (biases nullable)
+ *   y1 = act(W1 h + b1),  y2 = act(W2 y1 + b2),  s = w3 . y2 + b3
+ * act: 0 none (the paper calls the MLP "linear" and names no activation), 1 ReLU, 2 SiLU.
+ * Nothing is rounded between the layers.
+ */
+static double oracle_act(double x, int act) {
+  if (act == 1) return x > 0.0 ? x : 0.0;
+  if (act == 2) return x / (1.0 + exp(-x));
+  return x;
+}
+
+int dynts_oracle_predictor(int Nb, int d, int m1, int m2, const double *h, const double *W1,
+                           const double *b1, const double *W2, const double *b2, const double *w3,
+                           const double *b3, int act, double *s) {
+  if (Nb <= 0 || d <= 0 || m1 <= 0 || m2 <= 0 || act < 0 || act > 2) return -1;
+#pragma omp parallel for schedule(static)
+  for (int b = 0; b < Nb; ++b) {
+    double *y1 = (double *)malloc(sizeof(double) * (size_t)m1);
+    double *y2 = (double *)malloc(sizeof(double) * (size_t)m2);
+    for (int o = 0; o < m1; ++o) {
+      double acc = b1 ? b1[o] : 0.0;
+      for (int k = 0; k < d; ++k) acc += W1[(size_t)o * d + k] * h[(size_t)b * d + k];
+      y1[o] = oracle_act(acc, act);
+    }
+    for (int o = 0; o < m2; ++o) {
+      double acc = b2 ? b2[o] : 0.0;
+      for (int k = 0; k < m1; ++k) acc += W2[(size_t)o * m1 + k] * y1[k];
+      y2[o] = oracle_act(acc, act);
+    }
+    double acc = b3 ? b3[0] : 0.0;
+    for (int k = 0; k < m2; ++k) acc += w3[k] * y2[k];
+    s[b] = acc;
+    free(y1);
+    free(y2);
+  }
+  return 0;
+}
+
 /* ---- selection ---------------------------------------------------------- */
 
 typedef struct {

@@ -99,6 +99,21 @@ def score_block(q_blk, k_blk, K, seq_len, scale, active=None, I=None):
     return I
 
 
+ACT_NONE, ACT_RELU, ACT_SILU = 0, 1, 2
+
+
+def predictor(h, W1, b1, W2, b2, w3, b3, act=ACT_RELU):
+    """Importance Predictor MLP d -> m1 -> m2 -> 1 (Sec. 4.1, App. A): h [Nb][d] -> s [Nb]."""
+    Nb, d = h.shape
+    m1, m2 = W1.shape[0], W2.shape[0]
+    assert W1.shape == (m1, d) and W2.shape == (m2, m1) and w3.shape == (m2,)
+    s = np.zeros((Nb,), _f64)
+    _check(lib().dynts_oracle_predictor(Nb, d, m1, m2, _p(h, _f64), _p(W1, _f64), _p(b1, _f64), _p(W2, _f64),
+                                        _p(b2, _f64), _p(w3, _f64), _p(b3, _f64), int(act), _p(s, _f64)),
+           "predictor")
+    return s
+
+
 def select(S, pos, seq_len, n_prompt, window, k_keep, trigger=None, keep_stride=None):
     """Returns (keep_idx [Nb][Hkv][keep_stride] (-1 padded), new_len [Nb])."""
     Nb, Hkv, cap = S.shape
