@@ -194,6 +194,36 @@ int dynts_score_block(dynts_ctx *ctx, int32_t layer, const uint16_t *q_blk, cons
                       int32_t n_queries, const uint8_t *active, float *dst, int32_t accumulate,
                       void *scratch, size_t scratch_bytes, void *stream);
 
+/* Importance Predictor (Sec. 4.1; App. A "Predictor Overhead", App. C for the sizes): the three-layer
+ * MLP d -> m1 -> m2 -> 1 on the final hidden state of the current token,
+ *   s[b] = w3 . act(W2 act(W1 h[b] + b1) + b2) + b3,
+ * whose output is the score the paper's inference mode appends with the token (dynts_append / dynts_decode_step
+ * with score_mode DYNTS_SCORE_EXTERNAL take it as s_new).  Weights are device pointers, bf16 row-major
+ * [out][in]; biases fp32 or NULL.  The paper calls the MLP "linear" and names no activation: it is a
+ * parameter.  Products are accumulated in fp32 and nothing is rounded to bf16 between the layers.
+ *   h bf16 [batch][d], batch <= 128;  d and m1 multiples of 32, m2 a multiple of 16.
+ *   s_out fp32 [batch][n_rep]: the score of sequence b written n_rep times (n_rep = n_kv_heads gives the
+ *     [Nb][Hkv] layout of s_new: one score per token for every head, as in the paper).
+ *   scratch: >= dynts_predict_scratch_bytes bytes, 256-byte aligned, contents irrelevant.
+ *   start/stop: optional hipEvent_t handles attached to the first and the last kernel of the call. */
+#define DYNTS_ACT_NONE 0
+#define DYNTS_ACT_RELU 1
+#define DYNTS_ACT_SILU 2
+typedef struct dynts_predictor {
+  int32_t d, m1, m2;
+  int32_t activation; /* DYNTS_ACT_* */
+  const uint16_t *W1; /* [m1][d] */
+  const float *b1;    /* [m1] or NULL */
+  const uint16_t *W2; /* [m2][m1] */
+  const float *b2;    /* [m2] or NULL */
+  const uint16_t *w3; /* [m2] */
+  const float *b3;    /* [1] or NULL */
+} dynts_predictor;
+size_t dynts_predict_scratch_bytes(const dynts_predictor *w, int32_t batch);
+int dynts_predict_scores(const dynts_predictor *w, const uint16_t *h, int32_t batch, float *s_out,
+                         int32_t n_rep, void *scratch, size_t scratch_bytes, void *start, void *stop,
+                         void *stream);
+
 /* Measurement aid, not part of the method: one launch of a plain read stream over `bytes` (a multiple
  * of 16, buf 16-byte aligned) of device memory, 16 bytes per lane per load, n_workgroups x 256 lanes,
  * grid-stride.  Nothing is written unless the XOR of all words equals `magic` (then sink[0], one

@@ -23,7 +23,17 @@ EXPORTS = [
     "dynts_decode_attend_update", "dynts_decode_step", "dynts_select_evict", "dynts_compact",
     "dynts_decode_loop", "dynts_set_kernel_events", "dynts_set_kernel_event_list", "dynts_probe_read_stream",
     "dynts_score_block_scratch_bytes", "dynts_score_block",
+    "dynts_predict_scratch_bytes", "dynts_predict_scores",
 ]
+
+
+class dynts_predictor(C.Structure):
+    _fields_ = [("d", C.c_int32), ("m1", C.c_int32), ("m2", C.c_int32), ("activation", C.c_int32),
+                ("W1", C.c_void_p), ("b1", C.c_void_p), ("W2", C.c_void_p), ("b2", C.c_void_p),
+                ("w3", C.c_void_p), ("b3", C.c_void_p)]
+
+
+DYNTS_ACT_NONE, DYNTS_ACT_RELU, DYNTS_ACT_SILU = 0, 1, 2
 
 
 class dynts_config(C.Structure):
@@ -62,6 +72,9 @@ def _load():
     lib.dynts_score_block_scratch_bytes.restype = sz
     lib.dynts_score_block_scratch_bytes.argtypes = [C.POINTER(dynts_config), i32]
     lib.dynts_score_block.argtypes = [vp, i32, vp, vp, i32, vp, vp, i32, vp, sz, vp]
+    lib.dynts_predict_scratch_bytes.restype = sz
+    lib.dynts_predict_scratch_bytes.argtypes = [C.POINTER(dynts_predictor), i32]
+    lib.dynts_predict_scores.argtypes = [C.POINTER(dynts_predictor), vp, i32, vp, i32, vp, sz, vp, vp, vp]
     lib.dynts_probe_read_stream.argtypes = [vp, sz, i32, C.c_uint32, vp, vp, vp, vp]
     for name in EXPORTS:
         getattr(lib, name)
@@ -220,6 +233,33 @@ def dynts_score_block(ctx, layer, q_blk, k_blk, scratch, dst=None, accumulate=Tr
                                  _ptr(active, torch.uint8), _ptr(dst, torch.float32), 1 if accumulate else 0,
                                  scratch.data_ptr(), scratch.numel() * scratch.element_size(), _stream(stream)),
            "dynts_score_block")
+
+
+class Predictor:
+    """The Importance Predictor's weights (device tensors, kept alive here) and its scratch; marshalling only."""
+
+    def __init__(self, W1, b1, W2, b2, w3, b3, activation=DYNTS_ACT_RELU, max_batch=128):
+        self.t = (W1, b1, W2, b2, w3, b3)
+        m1, d = W1.shape
+        m2 = W2.shape[0]
+        assert W2.shape == (m2, m1) and w3.shape == (m2,)
+        self.w = dynts_predictor(d, m1, m2, activation, _ptr(W1, torch.bfloat16), _ptr(b1, torch.float32),
+                                 _ptr(W2, torch.bfloat16), _ptr(b2, torch.float32), _ptr(w3, torch.bfloat16),
+                                 _ptr(b3, torch.float32))
+        need = max(dynts_predict_scratch_bytes(self.w, nb) for nb in (16, 32, 64, max_batch) if nb <= max_batch)
+        self.scratch = torch.empty(max(need, 256), dtype=torch.uint8, device=W1.device)
+
+
+def dynts_predict_scratch_bytes(w, batch):
+    return int(lib.dynts_predict_scratch_bytes(C.byref(w), batch))
+
+
+def dynts_predict_scores(pred, h, s_out, start=None, stop=None, stream=None):
+    """pred: Predictor; h bf16 [Nb][d]; s_out fp32 [Nb][n_rep] (or [Nb])."""
+    n_rep = s_out.shape[1] if s_out.dim() == 2 else 1
+    _check(lib.dynts_predict_scores(C.byref(pred.w), _ptr(h, torch.bfloat16), h.shape[0], _ptr(s_out, torch.float32),
+                                    n_rep, pred.scratch.data_ptr(), pred.scratch.numel(), start, stop,
+                                    _stream(stream)), "dynts_predict_scores")
 
 
 def dynts_probe_read_stream(buf, n_workgroups, sink, start=None, stop=None, magic=0x9E3779B9, stream=None):

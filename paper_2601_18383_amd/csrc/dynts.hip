@@ -13,6 +13,7 @@
 
 #include "attend.hpp"
 #include "compact.hpp"
+#include "predictor.hpp"
 #include "probe.hpp"
 #include "score_block.hpp"
 #include "select.hpp"
@@ -207,6 +208,72 @@ int run_attend(dynts_ctx *ctx, int layer, const uint16_t *q, const uint16_t *k_n
   const int rc = launch_status();
   if (rc == DYNTS_OK && attend && track) ctx->qslot[layer] ^= 1;  // the query just saved becomes the current one
   return rc;
+}
+
+
+// ---- Importance Predictor ---------------------------------------------------------------------------
+struct MlpPlan {
+  int bt;               // batch tiles of 16
+  int nsplit;           // workgroups along K
+  int steps_per_split;  // k-steps of 32 per workgroup
+};
+
+MlpPlan mlp_plan(int batch, int K, int m, int parts) {
+  MlpPlan pl;
+  pl.bt = batch <= 16 ? 1 : batch <= 32 ? 2 : batch <= 64 ? 4 : 8;
+  int kcs = 256 / (parts * 16 * pl.bt);
+  if (kcs < 1) kcs = 1;
+  const int n_steps = K / 32;
+  const int groups = (m + dynts::kMlpFeaturesPerWg - 1) / dynts::kMlpFeaturesPerWg;
+  int want = (384 + groups - 1) / groups;            // enough workgroups for 256 CUs
+  int max_split = n_steps / (2 * kcs);               // at least two chunks per workgroup
+  if (max_split < 1) max_split = 1;
+  if (want > max_split) want = max_split;
+  int per = (n_steps + want - 1) / want;
+  per = (per + kcs - 1) / kcs * kcs;
+  pl.steps_per_split = per;
+  pl.nsplit = (n_steps + per - 1) / per;
+  return pl;
+}
+
+int check_predictor(const dynts_predictor *w, int batch) {
+  if (!w) return DYNTS_ENULL;
+  if (batch <= 0 || batch > 128) return DYNTS_EINVAL;
+  if (w->d <= 0 || w->m1 <= 0 || w->m2 <= 0) return DYNTS_EINVAL;
+  if (w->d % 32 || w->m1 % 32 || w->m2 % 16) return DYNTS_ESHAPE;
+  if (w->activation < DYNTS_ACT_NONE || w->activation > DYNTS_ACT_SILU) return DYNTS_EINVAL;
+  return DYNTS_OK;
+}
+
+struct MlpScratch {
+  size_t off_p1, off_yhi, off_ylo, off_p2, total;
+};
+
+MlpScratch mlp_scratch(const dynts_predictor *w, int batch, const MlpPlan &l1, const MlpPlan &l2) {
+  MlpScratch sc;
+  size_t off = 0;
+  sc.off_p1 = off;
+  off += align_up((size_t)l1.nsplit * batch * w->m1 * sizeof(float));
+  sc.off_yhi = off;
+  off += align_up((size_t)batch * w->m1 * sizeof(uint16_t));
+  sc.off_ylo = off;
+  off += align_up((size_t)batch * w->m1 * sizeof(uint16_t));
+  sc.off_p2 = off;
+  off += align_up((size_t)l2.nsplit * batch * w->m2 * sizeof(float));
+  sc.total = off;
+  return sc;
+}
+
+template <int PARTS>
+void launch_mlp_gemm(const dynts::MlpGemmParams &p, const MlpPlan &pl, hipStream_t st, hipEvent_t e0, hipEvent_t e1) {
+  const dim3 grid((p.m + dynts::kMlpFeaturesPerWg - 1) / dynts::kMlpFeaturesPerWg, pl.nsplit);
+  const dim3 block(dynts::kMlpThreads);
+  switch (pl.bt) {
+    case 1: hipExtLaunchKernelGGL((dynts::mlp_gemm_kernel<1, PARTS>), grid, block, 0, st, e0, e1, 0, p); break;
+    case 2: hipExtLaunchKernelGGL((dynts::mlp_gemm_kernel<2, PARTS>), grid, block, 0, st, e0, e1, 0, p); break;
+    case 4: hipExtLaunchKernelGGL((dynts::mlp_gemm_kernel<4, PARTS>), grid, block, 0, st, e0, e1, 0, p); break;
+    default: hipExtLaunchKernelGGL((dynts::mlp_gemm_kernel<8, PARTS>), grid, block, 0, st, e0, e1, 0, p); break;
+  }
 }
 
 }  // namespace
@@ -487,6 +554,43 @@ int dynts_score_block(dynts_ctx *ctx, int32_t layer, const uint16_t *q_blk, cons
     hipLaunchKernelGGL(dynts::score_block_stats_kernel<64>, g1, dim3(dynts::kSbWaves * 64), 0, st, p);
     hipLaunchKernelGGL(dynts::score_block_colsum_kernel<64>, g2, dim3(dynts::kSbWaves * 64), 0, st, p);
   }
+  return launch_status();
+}
+
+size_t dynts_predict_scratch_bytes(const dynts_predictor *w, int32_t batch) {
+  if (check_predictor(w, batch) != DYNTS_OK) return 0;
+  const MlpPlan l1 = mlp_plan(batch, w->d, w->m1, 1), l2 = mlp_plan(batch, w->m1, w->m2, 2);
+  return mlp_scratch(w, batch, l1, l2).total;
+}
+
+int dynts_predict_scores(const dynts_predictor *w, const uint16_t *h, int32_t batch, float *s_out, int32_t n_rep,
+                         void *scratch, size_t scratch_bytes, void *start, void *stop, void *stream) {
+  int rc = check_predictor(w, batch);
+  if (rc != DYNTS_OK) return rc;
+  if (!h || !s_out || !scratch || !w->W1 || !w->W2 || !w->w3) return DYNTS_ENULL;
+  if (n_rep <= 0 || n_rep > 256) return DYNTS_EINVAL;
+  if ((start == nullptr) != (stop == nullptr)) return DYNTS_EINVAL;
+  if (reinterpret_cast<uintptr_t>(h) % 16 || reinterpret_cast<uintptr_t>(w->W1) % 16 ||
+      reinterpret_cast<uintptr_t>(w->W2) % 16)
+    return DYNTS_EINVAL;
+  const MlpPlan l1 = mlp_plan(batch, w->d, w->m1, 1), l2 = mlp_plan(batch, w->m1, w->m2, 2);
+  const MlpScratch sc = mlp_scratch(w, batch, l1, l2);
+  if (scratch_bytes < sc.total || reinterpret_cast<uintptr_t>(scratch) % kAlign) return DYNTS_EWORKSPACE;
+  unsigned char *base = static_cast<unsigned char *>(scratch);
+  float *P1 = reinterpret_cast<float *>(base + sc.off_p1), *P2 = reinterpret_cast<float *>(base + sc.off_p2);
+  uint16_t *yhi = reinterpret_cast<uint16_t *>(base + sc.off_yhi), *ylo = reinterpret_cast<uint16_t *>(base + sc.off_ylo);
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  // the optional events bracket the whole call: start on the first kernel, stop on the last
+  dynts::MlpGemmParams g1{w->W1, h, nullptr, P1, batch, w->m1, w->d, l1.steps_per_split};
+  launch_mlp_gemm<1>(g1, l1, st, static_cast<hipEvent_t>(start), nullptr);
+  const size_t n1 = (size_t)batch * w->m1 / 4;
+  hipLaunchKernelGGL(dynts::mlp_reduce_act_kernel, dim3((unsigned)((n1 + 255) / 256)), dim3(256), 0, st, P1, w->b1,
+                     l1.nsplit, batch, w->m1, w->activation, yhi, ylo);
+  dynts::MlpGemmParams g2{w->W2, yhi, ylo, P2, batch, w->m2, w->m1, l2.steps_per_split};
+  launch_mlp_gemm<2>(g2, l2, st, nullptr, nullptr);
+  hipExtLaunchKernelGGL(dynts::mlp_reduce_dot_kernel, dim3(batch), dim3(256), 0, st, nullptr,
+                        static_cast<hipEvent_t>(stop), 0, P2, w->b2, l2.nsplit, batch, w->m2, w->activation, w->w3,
+                        w->b3, s_out, n_rep);
   return launch_status();
 }
 
