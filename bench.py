@@ -342,6 +342,52 @@ def run_score_block(args, wl):
                 first_timed_step=0, active_min=wl.batch, active_max=wl.batch)
 
 
+def run_predictor(args, wl):
+    """The Importance Predictor head with synthetic weights at the size of the workload's model shape
+    (28 query heads: 3584 -> 7168 -> 1792 -> 1, else 4096 -> 8192 -> 2048 -> 1), one score per sequence
+    written once per KV head (the layout dynts_decode_step takes as s_new).  A step is one call."""
+    import torch
+    from paper_2601_18383_amd import binding as B
+
+    dev = torch.device("cuda:0")
+    d = 3584 if wl.n_q_heads == 28 else 4096
+    m1, m2, nb = 2 * d, d // 2, min(wl.batch, 128)
+    g = torch.Generator(device="cpu").manual_seed(wl.seed)
+    rnd = lambda *shape: torch.randn(*shape, generator=g)
+    W1 = (rnd(m1, d) / d ** 0.5).to(torch.bfloat16).to(dev)
+    W2 = (rnd(m2, m1) / m1 ** 0.5).to(torch.bfloat16).to(dev)
+    w3 = (rnd(m2) / m2 ** 0.5).to(torch.bfloat16).to(dev)
+    b1, b2, b3 = (rnd(m1) * 0.1).to(dev), (rnd(m2) * 0.1).to(dev), rnd(1).to(dev)
+    pred = B.Predictor(W1, b1, W2, b2, w3, b3, activation=B.DYNTS_ACT_RELU, max_batch=nb)
+    n_pool = 8  # rotate hidden states; the weights are the traffic
+    hs = [rnd(nb, d).to(torch.bfloat16).to(dev) for _ in range(n_pool)]
+    s = torch.zeros((nb, wl.n_kv_heads), dtype=torch.float32, device=dev)
+    for i in range(args.warmup):
+        B.dynts_predict_scores(pred, hs[i % n_pool], s)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in range(args.steps):
+        B.dynts_predict_scores(pred, hs[i % n_pool], s)
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    n_ev = min(args.steps, 64)
+    ev = HipEvents(n_ev)
+    for i in range(n_ev):
+        B.dynts_predict_scores(pred, hs[i % n_pool], s, ev.pairs[i][0], ev.pairs[i][1])
+    torch.cuda.synchronize()
+    call_ms = sum(ev.elapsed_ms(i) for i in range(n_ev)) / n_ev
+    ev.close()
+    alg = 2 * (m1 * d + m2 * m1 + m2) + 4 * (m1 + m2 + 1) + nb * d * 2 + nb * wl.n_kv_heads * 4
+    achieved = alg / (call_ms * 1e-3) / 1e9
+    roofline = {"bound": "hbm", "kernel": "mlp_gemm x2 + reductions (one dynts_predict_scores call)",
+                "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": None, "call_avg_us": round(call_ms * 1e3, 2),
+                "algorithmic_bytes_per_call": alg, "flops_per_call": 2.0 * nb * (m1 * d + m2 * m1 + m2)}
+    return dict(value=args.steps / dt, ms_per_step=dt / args.steps * 1e3, roofline=roofline, whole_step_gbs=alg / dt *
+                args.steps / 1e9, seq_steps_per_s=args.steps * nb / dt, evictions_timed=0, first_timed_step=0,
+                active_min=nb, active_max=nb, mode="Importance Predictor %d -> %d -> %d -> 1, batch %d" % (d, m1, m2, nb))
+
+
 def run_cpu_baseline(wl, budget_s=15.0):
     """The float64 oracle, as it stands, on the host cores: whole decode steps of the same
     workload from a generator-made steady state (one layer's worth scaled to all layers)."""
@@ -391,15 +437,17 @@ def run_cpu_baseline(wl, budget_s=15.0):
 def result_line(args, wl, r, cpu):
     """The one JSON object bench.py prints."""
     line = {
-        "metric": "block-scoring calls/sec, 1 MI355X" if getattr(args, "score_block", 0) else
+        "metric": "predictor calls/sec, 1 MI355X" if getattr(args, "predictor", False) else
+                  "block-scoring calls/sec, 1 MI355X" if getattr(args, "score_block", 0) else
                   "decode steps/sec (attn+score+evict), 1 MI355X", "value": round(r["value"], 2),
-        "unit": "calls/s" if getattr(args, "score_block", 0) else "decode steps/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "unit": "calls/s" if getattr(args, "score_block", 0) or getattr(args, "predictor", False) else "decode steps/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": round(r["ms_per_step"], 5), "higher_is_better": True, "scaling": "weak",
         "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
         "config": {"workload": "%s: %d layer(s), batch %d, %d q / %d kv heads, head_dim %d, prompt %d, budget %d, "
                                "window %d, evict every %d; %s, %d-%d of %d sequences active" %
                                (wl.name, wl.n_layers, wl.batch, wl.n_q_heads, wl.n_kv_heads, wl.head_dim, wl.prompt,
                                 wl.budget, wl.window, wl.evict_every,
+                                r["mode"] if "mode" in r else
                                 "block scoring of %d queries per sequence on a steady-state cache" % args.score_block
                                 if getattr(args, "score_block", 0) else
                                 "whole decode from the prompt" if args.trajectory else "steady state",
@@ -428,6 +476,8 @@ def main():
     ap.add_argument("--score-block", type=int, default=0, metavar="T",
                     help="time dynts_score_block for a block of T queries (with their keys) on a steady-state "
                          "cache instead of the decode path")
+    ap.add_argument("--predictor", action="store_true",
+                    help="time the Importance Predictor head (synthetic weights at the workload's model size)")
     ap.add_argument("--full-kv", action="store_true",
                     help="the comparison run without eviction: same inputs, a cache that holds every token, "
                          "attention only (no score is kept)")
@@ -451,7 +501,10 @@ def main():
                                  evict_every=1, external_scores=True)
         args.trajectory = True
     log("host cores: %d; workload %s" % (os.cpu_count(), wl))
-    if args.score_block:
+    if args.predictor:
+        r = run_predictor(args, wl)
+        args.no_cpu_baseline = True
+    elif args.score_block:
         r = run_score_block(args, wl)
         args.no_cpu_baseline = True
     elif args.trajectory:

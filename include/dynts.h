@@ -212,6 +212,7 @@ int dynts_score_block(dynts_ctx *ctx, int32_t layer, const uint16_t *q_blk, cons
 typedef struct dynts_predictor {
   int32_t d, m1, m2;
   int32_t activation; /* DYNTS_ACT_* */
+  int32_t packed;     /* 0: W1, W2 row-major [out][in]; 1: both in the tiled layout of dynts_predictor_pack */
   const uint16_t *W1; /* [m1][d] */
   const float *b1;    /* [m1] or NULL */
   const uint16_t *W2; /* [m2][m1] */
@@ -219,6 +220,11 @@ typedef struct dynts_predictor {
   const uint16_t *w3; /* [m2] */
   const float *b3;    /* [1] or NULL */
 } dynts_predictor;
+/* One-off repacking of a row-major bf16 weight matrix W [m][K] (m a multiple of 16, K of 32) into tiles of
+ * 16 rows x 32 columns stored contiguously, W_packed [m/16][K/32][16][32] (same size, must not alias W).
+ * With packed weights every load instruction of the GEMM reads one contiguous kilobyte instead of 16 pieces a
+ * whole weight row apart, which is what lets the weight stream run at memory speed. */
+int dynts_predictor_pack(const uint16_t *W, int32_t m, int32_t K, uint16_t *W_packed, void *stream);
 size_t dynts_predict_scratch_bytes(const dynts_predictor *w, int32_t batch);
 int dynts_predict_scores(const dynts_predictor *w, const uint16_t *h, int32_t batch, float *s_out,
                          int32_t n_rep, void *scratch, size_t scratch_bytes, void *start, void *stop,

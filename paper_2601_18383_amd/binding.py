@@ -23,13 +23,13 @@ EXPORTS = [
     "dynts_decode_attend_update", "dynts_decode_step", "dynts_select_evict", "dynts_compact",
     "dynts_decode_loop", "dynts_set_kernel_events", "dynts_set_kernel_event_list", "dynts_probe_read_stream",
     "dynts_score_block_scratch_bytes", "dynts_score_block",
-    "dynts_predict_scratch_bytes", "dynts_predict_scores",
+    "dynts_predict_scratch_bytes", "dynts_predict_scores", "dynts_predictor_pack",
 ]
 
 
 class dynts_predictor(C.Structure):
     _fields_ = [("d", C.c_int32), ("m1", C.c_int32), ("m2", C.c_int32), ("activation", C.c_int32),
-                ("W1", C.c_void_p), ("b1", C.c_void_p), ("W2", C.c_void_p), ("b2", C.c_void_p),
+                ("packed", C.c_int32), ("W1", C.c_void_p), ("b1", C.c_void_p), ("W2", C.c_void_p), ("b2", C.c_void_p),
                 ("w3", C.c_void_p), ("b3", C.c_void_p)]
 
 
@@ -74,6 +74,7 @@ def _load():
     lib.dynts_score_block.argtypes = [vp, i32, vp, vp, i32, vp, vp, i32, vp, sz, vp]
     lib.dynts_predict_scratch_bytes.restype = sz
     lib.dynts_predict_scratch_bytes.argtypes = [C.POINTER(dynts_predictor), i32]
+    lib.dynts_predictor_pack.argtypes = [vp, i32, i32, vp, vp]
     lib.dynts_predict_scores.argtypes = [C.POINTER(dynts_predictor), vp, i32, vp, i32, vp, sz, vp, vp, vp]
     lib.dynts_probe_read_stream.argtypes = [vp, sz, i32, C.c_uint32, vp, vp, vp, vp]
     for name in EXPORTS:
@@ -238,16 +239,27 @@ def dynts_score_block(ctx, layer, q_blk, k_blk, scratch, dst=None, accumulate=Tr
 class Predictor:
     """The Importance Predictor's weights (device tensors, kept alive here) and its scratch; marshalling only."""
 
-    def __init__(self, W1, b1, W2, b2, w3, b3, activation=DYNTS_ACT_RELU, max_batch=128):
-        self.t = (W1, b1, W2, b2, w3, b3)
+    def __init__(self, W1, b1, W2, b2, w3, b3, activation=DYNTS_ACT_RELU, max_batch=128, pack=True):
+        """W1 [m1][d], W2 [m2][m1] row-major bf16 device tensors; pack=True repacks them once (library kernel)."""
         m1, d = W1.shape
         m2 = W2.shape[0]
         assert W2.shape == (m2, m1) and w3.shape == (m2,)
-        self.w = dynts_predictor(d, m1, m2, activation, _ptr(W1, torch.bfloat16), _ptr(b1, torch.float32),
-                                 _ptr(W2, torch.bfloat16), _ptr(b2, torch.float32), _ptr(w3, torch.bfloat16),
-                                 _ptr(b3, torch.float32))
+        if pack:
+            W1, W2 = dynts_predictor_pack(W1), dynts_predictor_pack(W2)
+        self.t = (W1, b1, W2, b2, w3, b3)
+        self.w = dynts_predictor(d, m1, m2, activation, 1 if pack else 0, _ptr(W1, torch.bfloat16),
+                                 _ptr(b1, torch.float32), _ptr(W2, torch.bfloat16), _ptr(b2, torch.float32),
+                                 _ptr(w3, torch.bfloat16), _ptr(b3, torch.float32))
         need = max(dynts_predict_scratch_bytes(self.w, nb) for nb in (16, 32, 64, max_batch) if nb <= max_batch)
         self.scratch = torch.empty(max(need, 256), dtype=torch.uint8, device=W1.device)
+
+
+def dynts_predictor_pack(W, stream=None):
+    """Row-major bf16 device matrix -> the tiled layout (a new tensor of the same shape and size)."""
+    out = torch.empty_like(W)
+    _check(lib.dynts_predictor_pack(_ptr(W, torch.bfloat16), W.shape[0], W.shape[1], out.data_ptr(), _stream(stream)),
+           "dynts_predictor_pack")
+    return out
 
 
 def dynts_predict_scratch_bytes(w, batch):

@@ -213,26 +213,15 @@ int run_attend(dynts_ctx *ctx, int layer, const uint16_t *q, const uint16_t *k_n
 
 // ---- Importance Predictor ---------------------------------------------------------------------------
 struct MlpPlan {
-  int bt;               // batch tiles of 16
-  int nsplit;           // workgroups along K
-  int steps_per_split;  // k-steps of 32 per workgroup
+  int bt;      // batch tiles of 16
+  int nsplit;  // workgroups along K (each covers mlp_slice_steps k-steps)
 };
 
-MlpPlan mlp_plan(int batch, int K, int m, int parts) {
+MlpPlan mlp_plan(int batch, int K, int parts) {
   MlpPlan pl;
   pl.bt = batch <= 16 ? 1 : batch <= 32 ? 2 : batch <= 64 ? 4 : 8;
-  int kcs = 256 / (parts * 16 * pl.bt);
-  if (kcs < 1) kcs = 1;
-  const int n_steps = K / 32;
-  const int groups = (m + dynts::kMlpFeaturesPerWg - 1) / dynts::kMlpFeaturesPerWg;
-  int want = (384 + groups - 1) / groups;            // enough workgroups for 256 CUs
-  int max_split = n_steps / (2 * kcs);               // at least two chunks per workgroup
-  if (max_split < 1) max_split = 1;
-  if (want > max_split) want = max_split;
-  int per = (n_steps + want - 1) / want;
-  per = (per + kcs - 1) / kcs * kcs;
-  pl.steps_per_split = per;
-  pl.nsplit = (n_steps + per - 1) / per;
+  const int slice = dynts::mlp_slice_steps(pl.bt, parts);
+  pl.nsplit = (K / 32 + slice - 1) / slice;
   return pl;
 }
 
@@ -242,11 +231,12 @@ int check_predictor(const dynts_predictor *w, int batch) {
   if (w->d <= 0 || w->m1 <= 0 || w->m2 <= 0) return DYNTS_EINVAL;
   if (w->d % 32 || w->m1 % 32 || w->m2 % 16) return DYNTS_ESHAPE;
   if (w->activation < DYNTS_ACT_NONE || w->activation > DYNTS_ACT_SILU) return DYNTS_EINVAL;
+  if (w->packed != 0 && w->packed != 1) return DYNTS_EINVAL;
   return DYNTS_OK;
 }
 
 struct MlpScratch {
-  size_t off_p1, off_yhi, off_ylo, off_p2, total;
+  size_t off_p1, off_yhi, off_ylo, off_p2, off_part, off_cnt, total;
 };
 
 MlpScratch mlp_scratch(const dynts_predictor *w, int batch, const MlpPlan &l1, const MlpPlan &l2) {
@@ -260,19 +250,23 @@ MlpScratch mlp_scratch(const dynts_predictor *w, int batch, const MlpPlan &l1, c
   off += align_up((size_t)batch * w->m1 * sizeof(uint16_t));
   sc.off_p2 = off;
   off += align_up((size_t)l2.nsplit * batch * w->m2 * sizeof(float));
+  sc.off_part = off;
+  off += align_up((size_t)batch * ((w->m2 + 255) / 256) * sizeof(float));
+  sc.off_cnt = off;
+  off += align_up((size_t)batch * sizeof(uint32_t));
   sc.total = off;
   return sc;
 }
 
-template <int PARTS>
+template <int PARTS, bool PACKED>
 void launch_mlp_gemm(const dynts::MlpGemmParams &p, const MlpPlan &pl, hipStream_t st, hipEvent_t e0, hipEvent_t e1) {
   const dim3 grid((p.m + dynts::kMlpFeaturesPerWg - 1) / dynts::kMlpFeaturesPerWg, pl.nsplit);
   const dim3 block(dynts::kMlpThreads);
   switch (pl.bt) {
-    case 1: hipExtLaunchKernelGGL((dynts::mlp_gemm_kernel<1, PARTS>), grid, block, 0, st, e0, e1, 0, p); break;
-    case 2: hipExtLaunchKernelGGL((dynts::mlp_gemm_kernel<2, PARTS>), grid, block, 0, st, e0, e1, 0, p); break;
-    case 4: hipExtLaunchKernelGGL((dynts::mlp_gemm_kernel<4, PARTS>), grid, block, 0, st, e0, e1, 0, p); break;
-    default: hipExtLaunchKernelGGL((dynts::mlp_gemm_kernel<8, PARTS>), grid, block, 0, st, e0, e1, 0, p); break;
+    case 1: hipExtLaunchKernelGGL((dynts::mlp_gemm_kernel<1, PARTS, PACKED>), grid, block, 0, st, e0, e1, 0, p); break;
+    case 2: hipExtLaunchKernelGGL((dynts::mlp_gemm_kernel<2, PARTS, PACKED>), grid, block, 0, st, e0, e1, 0, p); break;
+    case 4: hipExtLaunchKernelGGL((dynts::mlp_gemm_kernel<4, PARTS, PACKED>), grid, block, 0, st, e0, e1, 0, p); break;
+    default: hipExtLaunchKernelGGL((dynts::mlp_gemm_kernel<8, PARTS, PACKED>), grid, block, 0, st, e0, e1, 0, p); break;
   }
 }
 
@@ -557,9 +551,20 @@ int dynts_score_block(dynts_ctx *ctx, int32_t layer, const uint16_t *q_blk, cons
   return launch_status();
 }
 
+int dynts_predictor_pack(const uint16_t *W, int32_t m, int32_t K, uint16_t *W_packed, void *stream) {
+  if (!W || !W_packed) return DYNTS_ENULL;
+  if (m <= 0 || K <= 0) return DYNTS_EINVAL;
+  if (m % 16 || K % 32) return DYNTS_ESHAPE;
+  if (reinterpret_cast<uintptr_t>(W) % 16 || reinterpret_cast<uintptr_t>(W_packed) % 16 || W == W_packed) return DYNTS_EINVAL;
+  const size_t pieces = (size_t)m * K / 8;
+  hipLaunchKernelGGL(dynts::mlp_pack_kernel, dim3((unsigned)((pieces + 255) / 256)), dim3(256), 0,
+                     static_cast<hipStream_t>(stream), W, m, K, W_packed);
+  return launch_status();
+}
+
 size_t dynts_predict_scratch_bytes(const dynts_predictor *w, int32_t batch) {
   if (check_predictor(w, batch) != DYNTS_OK) return 0;
-  const MlpPlan l1 = mlp_plan(batch, w->d, w->m1, 1), l2 = mlp_plan(batch, w->m1, w->m2, 2);
+  const MlpPlan l1 = mlp_plan(batch, w->d, 1), l2 = mlp_plan(batch, w->m1, 2);
   return mlp_scratch(w, batch, l1, l2).total;
 }
 
@@ -573,7 +578,7 @@ int dynts_predict_scores(const dynts_predictor *w, const uint16_t *h, int32_t ba
   if (reinterpret_cast<uintptr_t>(h) % 16 || reinterpret_cast<uintptr_t>(w->W1) % 16 ||
       reinterpret_cast<uintptr_t>(w->W2) % 16)
     return DYNTS_EINVAL;
-  const MlpPlan l1 = mlp_plan(batch, w->d, w->m1, 1), l2 = mlp_plan(batch, w->m1, w->m2, 2);
+  const MlpPlan l1 = mlp_plan(batch, w->d, 1), l2 = mlp_plan(batch, w->m1, 2);
   const MlpScratch sc = mlp_scratch(w, batch, l1, l2);
   if (scratch_bytes < sc.total || reinterpret_cast<uintptr_t>(scratch) % kAlign) return DYNTS_EWORKSPACE;
   unsigned char *base = static_cast<unsigned char *>(scratch);
@@ -581,16 +586,19 @@ int dynts_predict_scores(const dynts_predictor *w, const uint16_t *h, int32_t ba
   uint16_t *yhi = reinterpret_cast<uint16_t *>(base + sc.off_yhi), *ylo = reinterpret_cast<uint16_t *>(base + sc.off_ylo);
   hipStream_t st = static_cast<hipStream_t>(stream);
   // the optional events bracket the whole call: start on the first kernel, stop on the last
-  dynts::MlpGemmParams g1{w->W1, h, nullptr, P1, batch, w->m1, w->d, l1.steps_per_split};
-  launch_mlp_gemm<1>(g1, l1, st, static_cast<hipEvent_t>(start), nullptr);
+  dynts::MlpGemmParams g1{w->W1, h, nullptr, P1, batch, w->m1, w->d};
+  if (w->packed) launch_mlp_gemm<1, true>(g1, l1, st, static_cast<hipEvent_t>(start), nullptr);
+  else launch_mlp_gemm<1, false>(g1, l1, st, static_cast<hipEvent_t>(start), nullptr);
   const size_t n1 = (size_t)batch * w->m1 / 4;
   hipLaunchKernelGGL(dynts::mlp_reduce_act_kernel, dim3((unsigned)((n1 + 255) / 256)), dim3(256), 0, st, P1, w->b1,
-                     l1.nsplit, batch, w->m1, w->activation, yhi, ylo);
-  dynts::MlpGemmParams g2{w->W2, yhi, ylo, P2, batch, w->m2, w->m1, l2.steps_per_split};
-  launch_mlp_gemm<2>(g2, l2, st, nullptr, nullptr);
-  hipExtLaunchKernelGGL(dynts::mlp_reduce_dot_kernel, dim3(batch), dim3(256), 0, st, nullptr,
+                     l1.nsplit, batch, w->m1, w->activation, yhi, ylo, reinterpret_cast<uint32_t *>(base + sc.off_cnt));
+  dynts::MlpGemmParams g2{w->W2, yhi, ylo, P2, batch, w->m2, w->m1};
+  if (w->packed) launch_mlp_gemm<2, true>(g2, l2, st, nullptr, nullptr);
+  else launch_mlp_gemm<2, false>(g2, l2, st, nullptr, nullptr);
+  hipExtLaunchKernelGGL(dynts::mlp_reduce_dot_kernel, dim3((w->m2 + 255) / 256, batch), dim3(256), 0, st, nullptr,
                         static_cast<hipEvent_t>(stop), 0, P2, w->b2, l2.nsplit, batch, w->m2, w->activation, w->w3,
-                        w->b3, s_out, n_rep);
+                        w->b3, reinterpret_cast<float *>(base + sc.off_part),
+                        reinterpret_cast<uint32_t *>(base + sc.off_cnt), s_out, n_rep);
   return launch_status();
 }
 

@@ -5,10 +5,11 @@
 //
 // One GEMM kernel serves layers 1 and 2:  P[split][b][o] = sum_{k in split} W[o][k] * x[b][k].
 //   * Weights are the MFMA A operand (16 output features per wave), loaded straight from HBM into
-//     operand registers, a whole chunk of k-steps ahead.  Eight waves of a workgroup take eight
-//     neighbouring feature tiles and share the activations.
-//   * Activations are the B operand (batch as columns).  A chunk of them is fetched with coalesced
-//     loads into one of two padded LDS buffers and read back in operand layout by all eight waves.
+//     operand registers, 16 k-steps ahead.  The eight waves of a workgroup take eight neighbouring
+//     feature tiles and share the activations.
+//   * Activations are the B operand (batch as columns).  The workgroup's whole K slice of them is
+//     fetched once with coalesced loads into padded LDS and read back in operand layout by all eight
+//     waves.
 //     Layer 2 takes its input as two bf16 arrays (hi + lo of the fp32 activation), two MFMAs per
 //     weight fragment, so nothing is rounded to bf16 between the layers.
 //   * K is split across workgroups (grid.y) so that a few hundred workgroups exist; the fp32
@@ -25,7 +26,6 @@ namespace dynts {
 constexpr int kMlpWaves = 8;
 constexpr int kMlpThreads = kMlpWaves * 64;
 constexpr int kMlpFeaturesPerWg = 16 * kMlpWaves;
-constexpr int kMlpStageLoads = 2;  // 16-byte loads per thread and chunk of activations
 
 struct MlpGemmParams {
   const uint16_t *W;    // [m][K] bf16
@@ -33,7 +33,6 @@ struct MlpGemmParams {
   const uint16_t *x1;   // [Nb][K] bf16 lo part, or null
   float *P;             // [nsplit][Nb][m] partial sums
   int Nb, m, K;
-  int steps_per_split;  // k-steps (32 elements) per grid.y slice
 };
 
 __device__ __forceinline__ float mlp_act(float x, int act) {
@@ -50,113 +49,106 @@ __device__ __forceinline__ uint16_t f32_to_bf16(float x) {
 }
 __device__ __forceinline__ float bf16_to_f32(uint16_t v) { return __uint_as_float((uint32_t)v << 16); }
 
+// k-steps (32 elements of K) one workgroup covers: its whole slice of the activations sits in 64 KB of LDS
+constexpr int mlp_slice_steps(int bt, int parts) { return 64 / (parts * bt); }
+
 // BT = batch tiles of 16 (batch padded to 16 BT), PARTS = 1 (bf16 input) or 2 (hi + lo).
-// grid (ceil(m / 128), nsplit), 512 threads.
-template <int BT, int PARTS>
+// grid (ceil(m / 128), ceil(K / 32 / S)), 512 threads, S = mlp_slice_steps(BT, PARTS).
+// A workgroup fetches its slice of the activations once (all loads in flight together), parks it in
+// LDS, meets at ONE barrier, and then only streams weights: a ring of DEPTH weight fragments per lane
+// is kept in flight, so HBM latency is paid once per workgroup, not once per chunk.
+template <int BT, int PARTS, bool PACKED>
 __global__ __launch_bounds__(kMlpThreads) void mlp_gemm_kernel(const MlpGemmParams p) {
-  constexpr int NBP = 16 * BT;                                   // padded batch
-  constexpr int KCS = (256 / (PARTS * NBP)) > 0 ? 256 / (PARTS * NBP) : 1;  // k-steps per chunk
-  constexpr int KC = 32 * KCS;                                   // elements per chunk
-  constexpr int LROW = KC * 2 + 16;                              // padded LDS pitch of one batch row
-  constexpr int PIECES = KC / 8;                                 // 16-byte pieces per row and chunk
-  constexpr int NLD = (PARTS * NBP * PIECES + kMlpThreads - 1) / kMlpThreads;
-  __shared__ __attribute__((aligned(16))) char lds[2][PARTS * NBP * LROW];
+  constexpr int NBP = 16 * BT;                       // padded batch
+  constexpr int S = mlp_slice_steps(BT, PARTS);      // k-steps per workgroup
+  constexpr int DEPTH = S < 16 ? S : 16;             // weight fragments in flight per lane
+  constexpr int LROW = S * 64 + 16;                  // padded LDS pitch of one batch row, bytes
+  constexpr int PIECES = S * 4;                      // 16-byte pieces per batch row
+  constexpr int NLD = PARTS * NBP * PIECES / kMlpThreads;  // = 8 staging loads per thread
+  static_assert(PARTS * NBP * PIECES % kMlpThreads == 0, "staging must divide evenly");
+  __shared__ __attribute__((aligned(16))) char lds[PARTS * NBP * LROW];
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int r16 = lane & 15, kg = lane >> 4;
   const int f0 = blockIdx.x * kMlpFeaturesPerWg + wave * 16;
   const bool has_rows = f0 < p.m;
   const int n_steps_all = p.K / 32;
-  const int s0 = blockIdx.y * p.steps_per_split;
-  int s1 = s0 + p.steps_per_split;
+  const int s0 = blockIdx.y * S;
+  int s1 = s0 + S;
   s1 = s1 < n_steps_all ? s1 : n_steps_all;
   if (s0 >= s1) return;  // uniform
-  const int n_chunks = (s1 - s0 + KCS - 1) / KCS;
+  const int n_steps = s1 - s0;
 
-  // this lane's weight row (rows past the last repeat it; their results are not written)
+  // this lane's weight fragments.  Row-major weights: 16 bytes of row f0 + r16 per k-step, i.e. 16 rows a
+  // whole weight row apart per load instruction.  Packed weights ([m/16][K/32][16][32], see
+  // mlp_pack_kernel): the 1 KB a load instruction needs is contiguous, and so is the whole slice.
+  // (Rows past the last repeat it; their results are not written.)
   int frow = f0 + r16;
   frow = frow < p.m ? frow : p.m - 1;
-  const char *Wrow = reinterpret_cast<const char *>(p.W + (size_t)frow * p.K) + 16 * kg;
-  const int last_step = s1 - 1;
+  const char *Wrow =
+      PACKED ? reinterpret_cast<const char *>(p.W + ((size_t)(frow >> 4) * n_steps_all + s0) * 512 + (frow & 15) * 32) + 16 * kg
+             : reinterpret_cast<const char *>(p.W + (size_t)frow * p.K + (size_t)s0 * 32) + 16 * kg;
+  constexpr size_t kStepBytes = PACKED ? 1024 : 64;
+  // first weight fragments on their way before anything else (steps past the slice repeat its last)
+  bf16x8 wf[DEPTH];
+#pragma unroll
+  for (int j = 0; j < DEPTH; ++j) {
+    const int st = j < n_steps ? j : n_steps - 1;
+    wf[j] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const u32x4 *>(Wrow + (size_t)st * kStepBytes));
+  }
 
-  // staging of the activations: piece q of the chunk = (part, batch row, 16-byte piece)
-  u32x4 stage[NLD];
-#define DYNTS_MLP_FETCH(chunk_)                                                                        \
-  _Pragma("unroll") for (int k = 0; k < NLD; ++k) {                                                    \
-    const int q = tid + kMlpThreads * k;                                                               \
-    if (q < PARTS * NBP * PIECES) {                                                                    \
-      const int part = q / (NBP * PIECES), rem = q - part * (NBP * PIECES);                            \
-      int row = rem / PIECES;                                                                          \
-      const int piece = rem - row * PIECES;                                                            \
-      row = row < p.Nb ? row : p.Nb - 1;                                                               \
-      int e = (s0 + (chunk_) * KCS) * 32 + 8 * piece;  /* element index along K */                     \
-      e = e < s1 * 32 ? e : s1 * 32 - 8;               /* past the slice: repeat its last piece */    \
-      const uint16_t *src = (PARTS == 2 && part == 1) ? p.x1 : p.x0;                                   \
-      stage[k] = *reinterpret_cast<const u32x4 *>(src + (size_t)row * p.K + e);                        \
-    }                                                                                                  \
+  // the slice of the activations: piece q = (part, batch row, 16-byte piece), coalesced along K
+  {
+    u32x4 stage[NLD];
+#pragma unroll
+    for (int k = 0; k < NLD; ++k) {
+      const int q = tid + kMlpThreads * k;
+      const int part = q / (NBP * PIECES), rem = q - part * (NBP * PIECES);
+      int row = rem / PIECES;
+      const int piece = rem - row * PIECES;
+      row = row < p.Nb ? row : p.Nb - 1;
+      int e = s0 * 32 + 8 * piece;
+      e = e < s1 * 32 ? e : s1 * 32 - 8;  // past the slice: repeat its last piece (never multiplied)
+      const uint16_t *src = (PARTS == 2 && part == 1) ? p.x1 : p.x0;
+      stage[k] = *reinterpret_cast<const u32x4 *>(src + (size_t)row * p.K + e);
+    }
+#pragma unroll
+    for (int k = 0; k < NLD; ++k) {
+      const int q = tid + kMlpThreads * k;
+      const int part = q / (NBP * PIECES), rem = q - part * (NBP * PIECES);
+      const int row = rem / PIECES, piece = rem - row * PIECES;
+      *reinterpret_cast<u32x4 *>(lds + (part * NBP + row) * LROW + 16 * piece) = stage[k];
+    }
   }
-#define DYNTS_MLP_PARK(buf_)                                                                           \
-  _Pragma("unroll") for (int k = 0; k < NLD; ++k) {                                                    \
-    const int q = tid + kMlpThreads * k;                                                               \
-    if (q < PARTS * NBP * PIECES) {                                                                    \
-      const int part = q / (NBP * PIECES), rem = q - part * (NBP * PIECES);                            \
-      const int row = rem / PIECES, piece = rem - row * PIECES;                                        \
-      *reinterpret_cast<u32x4 *>((buf_) + (part * NBP + row) * LROW + 16 * piece) = stage[k];          \
-    }                                                                                                  \
-  }
-  // weight fragments of one chunk (steps past the slice repeat the last step; they are skipped below)
-#define DYNTS_MLP_WLOAD(wf_, chunk_)                                                                   \
-  _Pragma("unroll") for (int ks = 0; ks < KCS; ++ks) {                                                 \
-    int st = s0 + (chunk_) * KCS + ks;                                                                 \
-    st = st < last_step ? st : last_step;                                                              \
-    wf_[ks] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const u32x4 *>(Wrow + (size_t)st * 64));    \
-  }
-#define DYNTS_MLP_COMPUTE(wf_, buf_, chunk_)                                                           \
-  if (has_rows) {                                                                                      \
-    _Pragma("unroll") for (int ks = 0; ks < KCS; ++ks) {                                               \
-      if (s0 + (chunk_) * KCS + ks < s1) { /* uniform */                                               \
-        _Pragma("unroll") for (int bt = 0; bt < BT; ++bt) {                                            \
-          _Pragma("unroll") for (int part = 0; part < PARTS; ++part) {                                 \
-            const bf16x8 xf = __builtin_bit_cast(bf16x8, *reinterpret_cast<const u32x4 *>(             \
-                (buf_) + (part * NBP + 16 * bt + r16) * LROW + 64 * ks + 16 * kg));                    \
-            acc[bt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(wf_[ks], xf, acc[bt], 0, 0, 0);          \
-          }                                                                                            \
-        }                                                                                              \
-      }                                                                                                \
-    }                                                                                                  \
-  }
+  __syncthreads();
+  if (!has_rows) return;
 
   f32x4 acc[BT];
 #pragma unroll
   for (int bt = 0; bt < BT; ++bt) acc[bt] = f32x4{0.f, 0.f, 0.f, 0.f};
-  bf16x8 wa[KCS], wb[KCS];
-
-  DYNTS_MLP_FETCH(0)
-  DYNTS_MLP_WLOAD(wa, 0)
-  DYNTS_MLP_PARK(lds[0])
-  if (n_chunks > 1) { DYNTS_MLP_FETCH(1) }
-  __syncthreads();
-  for (int ch = 0; ch < n_chunks; ch += 2) {
-    // even chunk: weights in wa, activations in lds[0]
-    if (ch + 1 < n_chunks) { DYNTS_MLP_WLOAD(wb, ch + 1) }
-    DYNTS_MLP_COMPUTE(wa, lds[0], ch)
-    if (ch + 1 < n_chunks) { DYNTS_MLP_PARK(lds[1]) }
-    if (ch + 2 < n_chunks) { DYNTS_MLP_FETCH(ch + 2) }
-    __syncthreads();
-    if (ch + 1 >= n_chunks) break;
-    // odd chunk: weights in wb, activations in lds[1]
-    if (ch + 2 < n_chunks) { DYNTS_MLP_WLOAD(wa, ch + 2) }
-    DYNTS_MLP_COMPUTE(wb, lds[1], ch + 1)
-    if (ch + 2 < n_chunks) { DYNTS_MLP_PARK(lds[0]) }
-    if (ch + 3 < n_chunks) { DYNTS_MLP_FETCH(ch + 3) }
-    __syncthreads();
+  for (int sb = 0; sb < n_steps; sb += DEPTH) {
+#pragma unroll
+    for (int j = 0; j < DEPTH; ++j) {
+      const int st = sb + j;
+      if (st < n_steps) {  // uniform
+#pragma unroll
+        for (int bt = 0; bt < BT; ++bt) {
+#pragma unroll
+          for (int part = 0; part < PARTS; ++part) {
+            const bf16x8 xf = __builtin_bit_cast(bf16x8, *reinterpret_cast<const u32x4 *>(
+                lds + (part * NBP + 16 * bt + r16) * LROW + 64 * st + 16 * kg));
+            acc[bt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(wf[j], xf, acc[bt], 0, 0, 0);
+          }
+        }
+      }
+      if (S > DEPTH) {  // refill this ring slot with the fragment DEPTH steps ahead
+        int nx = st + DEPTH;
+        nx = nx < n_steps ? nx : n_steps - 1;
+        wf[j] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const u32x4 *>(Wrow + (size_t)nx * kStepBytes));
+      }
+    }
   }
-#undef DYNTS_MLP_FETCH
-#undef DYNTS_MLP_PARK
-#undef DYNTS_MLP_WLOAD
-#undef DYNTS_MLP_COMPUTE
 
   // acc[bt][i]: feature f0 + 4 kg + i, batch 16 bt + r16
-  if (!has_rows) return;
   const int f = f0 + 4 * kg;
 #pragma unroll
   for (int bt = 0; bt < BT; ++bt) {
@@ -168,14 +160,33 @@ __global__ __launch_bounds__(kMlpThreads) void mlp_gemm_kernel(const MlpGemmPara
   }
 }
 
+// Row-major bf16 weights [m][K] -> tiles of 16 rows x 32 columns stored contiguously, [m/16][K/32][16][32]:
+// what one MFMA A-operand load of a wave reads becomes one contiguous kilobyte.  One-off, at load time.
+// grid (ceil(m * K / 8 / 256)), 256 threads, 16 bytes per thread.
+__global__ __launch_bounds__(256) void mlp_pack_kernel(const uint16_t *W, int m, int K, uint16_t *Wp) {
+  const size_t piece = (size_t)blockIdx.x * 256 + threadIdx.x;  // 16-byte piece of the packed array
+  if (piece >= (size_t)m * K / 8) return;
+  const size_t e = piece * 8;                  // element index in the packed array
+  const int c = (int)(e % 32), r = (int)((e / 32) % 16);
+  const size_t ts = e / 512;                   // tile * n_steps + step
+  const int n_steps = K / 32;
+  const size_t tile = ts / n_steps, step = ts % n_steps;
+  *reinterpret_cast<u32x4 *>(Wp + e) =
+      *reinterpret_cast<const u32x4 *>(W + (tile * 16 + r) * (size_t)K + step * 32 + c);
+}
+
 // y = act(sum over splits of P + bias), written as bf16 hi and lo parts for the next layer.
 // grid (ceil(Nb * m / 4 / 256)), 256 threads, 4 features per thread.
 __global__ __launch_bounds__(256) void mlp_reduce_act_kernel(const float *P, const float *bias, int nsplit, int Nb,
-                                                             int m, int act, uint16_t *y_hi, uint16_t *y_lo) {
+                                                             int m, int act, uint16_t *y_hi, uint16_t *y_lo,
+                                                             uint32_t *row_cnt) {
+  // (the arrival counters of the final kernel of this call start from zero: stream order puts this first)
+  if (blockIdx.x == 0 && (int)threadIdx.x < Nb) row_cnt[threadIdx.x] = 0;
   const size_t idx = ((size_t)blockIdx.x * 256 + threadIdx.x) * 4;
   if (idx >= (size_t)Nb * m) return;
   const int o = (int)(idx % m);
   f32x4 v = *reinterpret_cast<const f32x4 *>(P + idx);
+#pragma unroll 4
   for (int s = 1; s < nsplit; ++s) v += *reinterpret_cast<const f32x4 *>(P + (size_t)s * Nb * m + idx);
   uint16_t hi[4], lo[4];
 #pragma unroll
@@ -188,23 +199,39 @@ __global__ __launch_bounds__(256) void mlp_reduce_act_kernel(const float *P, con
   *reinterpret_cast<uint2 *>(y_lo + idx) = make_uint2(lo[0] | ((uint32_t)lo[1] << 16), lo[2] | ((uint32_t)lo[3] << 16));
 }
 
-// s[b] = w3 . act(sum over splits of P[.][b][:] + bias) + b3, written n_rep times.  grid (Nb), 256 threads.
+// s[b] = w3 . act(sum over splits of P[.][b][:] + bias) + b3, written n_rep times.
+// grid (ceil(m / 256), Nb), 256 threads: a workgroup takes 256 features of one sequence and leaves its part of
+// the dot product in part[b][blockIdx.x]; the last workgroup of a sequence to arrive (device counter) adds the
+// parts in index order, so the result does not depend on the arrival order.
 __global__ __launch_bounds__(256) void mlp_reduce_dot_kernel(const float *P, const float *bias, int nsplit, int Nb,
                                                              int m, int act, const uint16_t *w3, const float *b3,
-                                                             float *s_out, int n_rep) {
+                                                             float *part, uint32_t *row_cnt, float *s_out, int n_rep) {
   __shared__ float red[4];
-  const int b = blockIdx.x, tid = threadIdx.x;
-  float acc = 0.f;
-  for (int o = tid; o < m; o += 256) {
+  __shared__ int is_last;
+  const int b = blockIdx.y, tid = threadIdx.x, o = blockIdx.x * 256 + tid;
+  float t = 0.f;
+  if (o < m) {
     float v = 0.f;
+#pragma unroll 8
     for (int s = 0; s < nsplit; ++s) v += P[((size_t)s * Nb + b) * m + o];
-    acc += bf16_to_f32(w3[o]) * mlp_act(v + (bias ? bias[o] : 0.f), act);
+    t = bf16_to_f32(w3[o]) * mlp_act(v + (bias ? bias[o] : 0.f), act);
   }
 #pragma unroll
-  for (int sh = 32; sh >= 1; sh >>= 1) acc += __shfl_xor(acc, sh);
-  if ((tid & 63) == 0) red[tid >> 6] = acc;
+  for (int sh = 32; sh >= 1; sh >>= 1) t += __shfl_xor(t, sh);
+  if ((tid & 63) == 0) red[tid >> 6] = t;
   __syncthreads();
-  if (tid < n_rep) s_out[(size_t)b * n_rep + tid] = red[0] + red[1] + red[2] + red[3] + (b3 ? b3[0] : 0.f);
+  if (tid == 0) {
+    coherent_store(part + (size_t)b * gridDim.x + blockIdx.x, (red[0] + red[1]) + (red[2] + red[3]));
+    wait_own_stores();
+    is_last = atomicAdd(row_cnt + b, 1u) == gridDim.x - 1;
+  }
+  __syncthreads();
+  if (!is_last) return;
+  if (tid < n_rep) {
+    float tot = 0.f;
+    for (unsigned k = 0; k < gridDim.x; ++k) tot += coherent_load(part + (size_t)b * gridDim.x + k);
+    s_out[(size_t)b * n_rep + tid] = tot + (b3 ? b3[0] : 0.f);
+  }
 }
 
 }  // namespace dynts

@@ -26,11 +26,11 @@ def _make(rng, d, m1, m2, bias=True):
     return W1, b1, W2, b2, w3, b3
 
 
-def _run(B, rng, d, m1, m2, batch, act, bias=True, n_rep=1):
+def _run(B, rng, d, m1, m2, batch, act, bias=True, n_rep=1, pack=True):
     dev = torch.device("cuda:0")
     ws = _make(rng, d, m1, m2, bias)
     h = torch.from_numpy(rng.standard_normal((batch, d)).astype(np.float32)).to(torch.bfloat16)
-    pred = B.Predictor(*[w.to(dev) if w is not None else None for w in ws], activation=act)
+    pred = B.Predictor(*[w.to(dev) if w is not None else None for w in ws], activation=act, pack=pack)
     s = torch.full((batch, n_rep), 7.0, dtype=torch.float32, device=dev)
     B.dynts_predict_scores(pred, h.to(dev), s)
     ref = orc.predictor(f64(h), *[f64(w) if w is not None else None for w in ws], act)
@@ -48,7 +48,7 @@ def test_small_shapes(B, d, m1, m2, batch, act):
     """Ragged feature groups (m not a multiple of 128), K slices with a partial last chunk, every batch-tile
     variant of the kernel, with and without biases."""
     rng = np.random.default_rng(d + batch + act)
-    _run(B, rng, d, m1, m2, batch, act, bias=(batch % 2 == 1), n_rep=1 + batch % 4)
+    _run(B, rng, d, m1, m2, batch, act, bias=(batch % 2 == 1), n_rep=1 + batch % 4, pack=(act != 1))
 
 
 @pytest.mark.parametrize("d,batch,hkv", [(3584, 32, 4), (4096, 64, 8), (4096, 128, 8)])
@@ -57,6 +57,21 @@ def test_paper_sizes(B, d, batch, hkv):
     benchmark configs, the score written once per KV head."""
     rng = np.random.default_rng(d + batch)
     _run(B, rng, d, 2 * d, d // 2, batch, orc.ACT_RELU, n_rep=hkv)
+
+
+def test_pack_is_the_documented_permutation(B):
+    """[m][K] -> [m/16][K/32][16][32], bit for bit."""
+    dev = torch.device("cuda:0")
+    m, K = 48, 96
+    W = torch.arange(m * K, dtype=torch.int32).reshape(m, K).to(torch.int16).view(torch.bfloat16).to(dev)
+    got = B.dynts_predictor_pack(W).view(torch.int16).cpu().numpy().reshape(m // 16, K // 32, 16, 32)
+    want = W.view(torch.int16).cpu().numpy().reshape(m // 16, 16, K // 32, 32).transpose(0, 2, 1, 3)
+    assert np.array_equal(got, want)
+
+
+def test_row_major_weights_at_paper_size(B):
+    rng = np.random.default_rng(5)
+    _run(B, rng, 3584, 7168, 1792, 32, orc.ACT_SILU, n_rep=4, pack=False)
 
 
 def test_argument_errors(B):
@@ -68,7 +83,7 @@ def test_argument_errors(B):
     s = torch.zeros((4, 300), dtype=torch.float32, device=dev)
     with pytest.raises(B.DyntsError):
         B.dynts_predict_scores(pred, h, s)                       # n_rep too large
-    bad = B.dynts_predictor(60, 128, 32, 1, 0, 0, 0, 0, 0, 0)    # d not a multiple of 32
+    bad = B.dynts_predictor(60, 128, 32, 1, 0, 0, 0, 0, 0, 0, 0)  # d not a multiple of 32
     assert B.dynts_predict_scratch_bytes(bad, 4) == 0
     assert B.dynts_predict_scratch_bytes(pred.w, 129) == 0
     assert B.dynts_predict_scratch_bytes(pred.w, 128) > 0
