@@ -186,12 +186,24 @@ def run_gpu(args, wl):
     if args.warmup:
         B.dynts_decode_loop(cache.ctx, args.warmup, qw, kw, vw, out, cache.keep_idx, cache.new_len, s_new=sw,
                             active=aw, evict_steps=fw, trigger=aw)
+    # the K timed steps go out as up to 8 windows of whole eviction periods, with an event between them on
+    # the launch stream (no host synchronisation inside the timed region)
+    n_win = max(1, min(8, args.steps // E))
+    win = args.steps // n_win // E * E if args.steps >= E else args.steps
+    bounds = [i * win for i in range(n_win)] + [args.steps]
+    marks = [torch.cuda.Event(enable_timing=True) for _ in range(n_win + 1)]
     torch.cuda.synchronize()
     t0 = time.perf_counter()
-    B.dynts_decode_loop(cache.ctx, args.steps, qt, kt, vt, out, cache.keep_idx, cache.new_len, s_new=stt,
-                        active=at, evict_steps=ft, trigger=at)
+    marks[0].record()
+    for i in range(n_win):
+        a, b = bounds[i], bounds[i + 1]
+        B.dynts_decode_loop(cache.ctx, b - a, qt[a:b], kt[a:b], vt[a:b], out, cache.keep_idx, cache.new_len,
+                            s_new=stt[a:b] if stt is not None else None, active=at[a:b] if at is not None else None,
+                            evict_steps=ft[a:b], trigger=at[a:b] if at is not None else None)
+        marks[i + 1].record()
     torch.cuda.synchronize()
     dt = time.perf_counter() - t0
+    win_ms = sorted(marks[i].elapsed_time(marks[i + 1]) / (bounds[i + 1] - bounds[i]) for i in range(n_win))
     t_end = t + args.warmup + args.steps
     assert int(cache.status[0]) == 0, "device status word set: %d" % int(cache.status[0])
     longest = int(lengths.argmax())
@@ -238,7 +250,9 @@ def run_gpu(args, wl):
     return dict(value=args.steps / dt, ms_per_step=dt / args.steps * 1e3, roofline=roofline,
                 whole_step_gbs=step_bytes / dt / 1e9, seq_steps_per_s=sum(act_counts) / dt,
                 evictions_timed=int(ft.sum()), first_timed_step=t + args.warmup + 1,
-                active_min=min(act_counts), active_max=max(act_counts))
+                active_min=min(act_counts), active_max=max(act_counts),
+                windows={"n": n_win, "steps_each": win, "ms_per_step_median": round(win_ms[len(win_ms) // 2], 5),
+                         "ms_per_step_min": round(win_ms[0], 5), "ms_per_step_max": round(win_ms[-1], 5)})
 
 
 def run_trajectory(args, wl):
@@ -427,7 +441,17 @@ def run_cpu_baseline(wl, budget_s=15.0):
             break
     dt = time.perf_counter() - t0
     layer_steps_per_s = done / dt
+    # the same oracle on one thread, a few more steps (bounded to ~5 s)
+    orc.set_threads(1)
+    one, t1 = 0, time.perf_counter()
+    while done + one < len(steps) and (one < 2 or time.perf_counter() - t1 < 5.0):
+        i = done + one
+        o.step(q[i], k[i], v[i], s[i] if s is not None else None)
+        one += 1
+    dt1 = time.perf_counter() - t1
+    orc.set_threads(threads)
     return {"value": layer_steps_per_s / wl.n_layers, "unit": "decode steps/s", "cores": threads,
+            "one_thread_value": (one / dt1 / wl.n_layers) if one else None,
             "kind": "oracle",
             "sample": "%d whole layer-steps (append+attend+score%s) of %s, full batch, from a synthetic steady "
                       "state of %d slots, %.1f s; divided by %d layers" %
@@ -453,7 +477,7 @@ def result_line(args, wl, r, cpu):
                                 "whole decode from the prompt" if args.trajectory else "steady state",
                                 r["active_min"], r["active_max"], wl.batch),
                    "first_timed_step": r["first_timed_step"], "evictions_in_window": r["evictions_timed"],
-                   "sequence_steps_per_s": round(r["seq_steps_per_s"], 1),
+                   "sequence_steps_per_s": round(r["seq_steps_per_s"], 1), "timed_windows": r.get("windows"),
                    "whole_step_algorithmic_GBps": round(r["whole_step_gbs"], 1)},
         "roofline": r["roofline"], "cpu_baseline": cpu,
     }
