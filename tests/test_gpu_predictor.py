@@ -87,3 +87,39 @@ def test_argument_errors(B):
     assert B.dynts_predict_scratch_bytes(bad, 4) == 0
     assert B.dynts_predict_scratch_bytes(pred.w, 129) == 0
     assert B.dynts_predict_scratch_bytes(pred.w, 128) > 0
+
+
+def test_paper_inference_mode_end_to_end(B):
+    """The paper's own inference loop (Sec. 4.1-4.2) in small: every step the predictor head turns the current
+    token's hidden state into one score, the token is appended with that score (the same for every KV head),
+    attention runs over the retained cache, and when the budget is reached the top-k by predicted score stay.
+    HIP path (predictor + fused decode step + selection + compaction) against the oracle chain."""
+    from tests.helpers import SideBySide
+    rng = np.random.default_rng(77)
+    dev = torch.device("cuda:0")
+    Nb, Hq, Hkv, d_head, M, budget, window, E = 3, 8, 2, 64, 11, 24, 16, 20
+    d_model, m1, m2 = 64, 128, 32
+    ws = _make(rng, d_model, m1, m2)
+    pred = B.Predictor(*[w.to(dev) for w in ws], activation=B.DYNTS_ACT_SILU)
+    cap = M + budget + window + E
+    cache = B.Cache(1, Nb, Hq, Hkv, d_head, cap, budget, window, E, external_scores=True)
+    o = orc.OracleLayer(Nb, Hq, Hkv, d_head, cap, budget, window, E, external_scores=True)
+    sbs = SideBySide(B, cache, 0, o, "step")
+    bf = lambda *shape: torch.from_numpy(rng.standard_normal(shape).astype(np.float32)).to(torch.bfloat16)
+    sbs.prefill(bf(Nb, Hkv, M, d_head), bf(Nb, Hkv, M, d_head), [M, 5, 8])
+    s_dev = torch.zeros((Nb, Hkv), dtype=torch.float32, device=dev)
+    T = budget + window + 3 * E + 7
+    for t in range(1, T + 1):
+        h = bf(Nb, d_model)
+        B.dynts_predict_scores(pred, h.to(dev), s_dev)
+        s_ref = orc.predictor(f64(h), *[f64(w) for w in ws], orc.ACT_SILU)
+        assert_close(f64(s_dev)[:, 0], s_ref, "predicted score, step %d" % t)
+        # both sides append the HIP path's fp32 score, so that the selection below is decided on identical
+        # numbers (the predictor's own parity is asserted just above)
+        sbs.step(bf(Nb, Hq, d_head), bf(Nb, Hkv, d_head), bf(Nb, Hkv, d_head), s=s_dev.cpu(), check_scores=(t % 9 == 0))
+    assert sbs.evictions == 3
+    sbs.check_state()
+    # external scores are never changed by attention: every retained thinking slot still holds its predicted score
+    S = f64(cache.S[0])
+    assert np.all(S[:, 0, :] == S[:, 1, :])
+    assert int(cache.status.item()) == 0
