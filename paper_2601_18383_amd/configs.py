@@ -87,5 +87,15 @@ CONFIGS["paper_llama_5000"] = paper_schedule("paper_llama_5000", 32, 8, 5000, 20
 CONFIGS["paper_llama_3000"] = paper_schedule("paper_llama_3000", 32, 8, 3000, 1000, 0.3, seed=0xD7A50014)
 
 
+# Other cache policies expressed through the same selection rule (Sec. 6.1 lists them as baselines; here
+# they only serve like-for-like kernel measurements on the cfg3 shape and streams):
+#  * sliding window with attention sinks (StreamingLLM-style): question slots + the most recent tokens,
+#    nothing selected by score -> budget 0, the whole thinking budget is the local window;
+#  * heavy-hitter eviction (H2O-style): accumulated attention as the score, a local window, and ONE token
+#    evicted per step once the cache is full -> evict_every 1.
+CONFIGS["policy_window"] = replace(CONFIGS["cfg3"], name="policy_window", budget=0, window=2176, evict_every=64)
+CONFIGS["policy_h2o"] = replace(CONFIGS["cfg3"], name="policy_h2o", budget=2048, window=128, evict_every=1)
+
+
 def get(name: str) -> Workload:
     return CONFIGS[name]

@@ -94,10 +94,11 @@ def _run(B, name, layers, sample, n_steps=3, n0_delta=0):
                 assert near_tie_ok(o.S[bi, h], wl.prompt, n1 - wl.window, keep_gpu[bi, h, :len_gpu[bi]].tolist(),
                                    keep_ref[bi, h, :len_ref[bi]].tolist())
         # the retained set is the best one by the GPU's own scores: properties that hold at any size
-        kk = keep_gpu[0, 0, wl.prompt:wl.prompt + wl.budget]
-        cand = S_gpu[0, 0, wl.prompt:n1 - wl.window]
-        cut = np.sort(cand)[::-1][wl.budget - 1]
-        assert np.all(S_gpu[0, 0, kk] >= cut) and np.all(np.diff(kk) > 0)
+        if wl.budget > 0:
+            kk = keep_gpu[0, 0, wl.prompt:wl.prompt + wl.budget]
+            cand = S_gpu[0, 0, wl.prompt:n1 - wl.window]
+            cut = np.sort(cand)[::-1][wl.budget - 1]
+            assert np.all(S_gpu[0, 0, kk] >= cut) and np.all(np.diff(kk) > 0)
         B.dynts_compact(cache.ctx, layer, cache.keep_idx, cache.new_len)
         o.compact(keep_same, len_same)
         n2 = wl.steady_len
@@ -146,6 +147,13 @@ def test_paper_budget_settings_full_shape(B):
     _run(B, "paper_qwen_5000", [0], [0, 31], n_steps=2, n0_delta=wl.evict_every - 2)
     wl = configs.get("paper_llama_3000")
     _run(B, "paper_llama_3000", [0], [7], n_steps=2, n0_delta=wl.evict_every - 2)
+
+
+def test_other_policies_full_shape(B):
+    """The same kernels under two other cache policies: sliding window with sinks (nothing kept by score) and
+    heavy-hitter eviction of one token per step."""
+    _run(B, "policy_window", [0], [3], n_steps=2, n0_delta=62)
+    _run(B, "policy_h2o", [0], [9, 30], n_steps=1, n0_delta=0)
 
 
 def test_ragged_batch_full_shape(B):
