@@ -223,3 +223,82 @@ def test_attention_edge_cases(B):
     assert np.array_equal(got[0, 0], f64(V0[0, 0, 0]))                 # n = 1: the value row itself
     assert np.allclose(got[1, 0], f64(V0[1, 0, 123]), atol=1e-6)      # one-hot
     assert np.allclose(got[3, 5], f64(V0[3, 1, :33]).mean(0), atol=2e-3)
+
+
+def test_degenerate_batches_and_limits(B):
+    """All sequences finished; an empty question window (the first token attends to itself alone); a full cache
+    (the append is dropped, the sequence is left alone and the status word says so)."""
+    rng = np.random.default_rng(12)
+    dev = torch.device("cuda:0")
+    Nb, Hq, Hkv, d = 3, 8, 2, 64
+    budget, window, E = 6, 2, 2
+    cap = 4 + budget + window + E
+    cache = B.Cache(1, Nb, Hq, Hkv, d, cap, budget, window, E)
+    o = orc.OracleLayer(Nb, Hq, Hkv, d, cap, budget, window, E)
+    sbs = SideBySide(B, cache, 0, o, "step")
+    sbs.prefill(_bf16(rng, Nb, Hkv, 4, d), _bf16(rng, Nb, Hkv, 4, d), [0, 4, 2])
+    # nobody is active: nothing moves
+    q, k, v = _bf16(rng, Nb, Hq, d), _bf16(rng, Nb, Hkv, d), _bf16(rng, Nb, Hkv, d)
+    before = (cache.K.clone(), cache.S.clone(), cache.seq_len.clone())
+    sbs.out.fill_(7.0)
+    B.dynts_decode_step(cache.ctx, 0, q.to(dev), k.to(dev), v.to(dev), sbs.out,
+                        active=torch.zeros(Nb, dtype=torch.uint8, device=dev))
+    B.dynts_update_scores(cache.ctx, 0)
+    assert torch.equal(cache.K, before[0]) and torch.equal(cache.S, before[1]) and torch.equal(cache.seq_len, before[2])
+    assert bool((sbs.out == 7.0).all())
+    # first real step: sequence 0 has no question tokens, its output is the new value row itself
+    sbs.step(q, k, v)
+    assert np.array_equal(f64(sbs.out)[0], np.repeat(f64(v)[0], Hq // Hkv, axis=0))
+    # run without evicting until sequence 1 (4 question tokens) fills the cache
+    for _ in range(cap - 4 - 1):
+        B.dynts_decode_step(cache.ctx, 0, q.to(dev), k.to(dev), v.to(dev), sbs.out)
+    assert int(cache.status.item()) == 0
+    assert i32(cache.seq_len[0]).tolist() == [cap - 4, cap, cap - 2]
+    B.dynts_update_scores(cache.ctx, 0)
+    snap = (cache.K.clone(), cache.seq_len.clone())
+    sbs.out.fill_(7.0)
+    B.dynts_decode_step(cache.ctx, 0, q.to(dev), k.to(dev), v.to(dev), sbs.out)
+    assert int(cache.status.item()) & 1                       # the append of sequence 1 was dropped ...
+    assert i32(cache.seq_len[0]).tolist() == [cap - 3, cap, cap - 1]
+    assert torch.equal(cache.K[0, 1], snap[0][0, 1])          # ... its rows are untouched ...
+    assert bool((sbs.out[1] == 7.0).all()) and not bool((sbs.out[0] == 7.0).any())   # ... and it was not attended
+    # the separate append call reports the same condition
+    cache.status.zero_()
+    B.dynts_update_scores(cache.ctx, 0)
+    B.dynts_append(cache.ctx, 0, k.to(dev), v.to(dev))
+    assert int(cache.status.item()) & 1 and i32(cache.seq_len[0]).tolist() == [cap - 2, cap, cap]
+
+
+def test_long_cache_single_unit(B):
+    """A cache of 40 000 slots for one (sequence, KV head): many splits, each wave a long range."""
+    rng = np.random.default_rng(13)
+    dev = torch.device("cuda:0")
+    Hq, Hkv, d, M = 4, 1, 128, 100
+    n0 = 39_987
+    cap = 40_000
+    cache = B.Cache(1, 1, Hq, Hkv, d, cap, cap - M - 20, 10, 10)
+    o = orc.OracleLayer(1, Hq, Hkv, d, cap, cap - M - 20, 10, 10)
+    K = _bf16(rng, 1, Hkv, n0, d)
+    V = _bf16(rng, 1, Hkv, n0, d)
+    S = torch.from_numpy(rng.random((1, Hkv, n0)).astype(np.float32))
+    S[:, :, :M] = float("inf")
+    cache.K[0, :, :, :n0] = K.to(dev); cache.V[0, :, :, :n0] = V.to(dev); cache.S[0, :, :, :n0] = S.to(dev)
+    cache.pos[0, :, :, :n0] = torch.arange(n0, dtype=torch.int32, device=dev)
+    cache.seq_len.fill_(n0); cache.next_pos.fill_(n0); cache.n_prompt.fill_(M)
+    o.K[:, :, :n0] = f64(K); o.V[:, :, :n0] = f64(V); o.S[:, :, :n0] = f64(S)
+    o.pos[:, :, :n0] = np.arange(n0); o.seq_len[:] = n0; o.next_pos[:] = n0; o.n_prompt[:] = M
+    sbs = SideBySide(B, cache, 0, o, "step")
+    for t in range(3):
+        sbs.step(_bf16(rng, 1, Hq, d, scale=1.5), _bf16(rng, 1, Hkv, d), _bf16(rng, 1, Hkv, d), check_scores=(t == 2))
+    assert int(cache.seq_len.item()) == n0 + 3 and int(cache.status.item()) == 0
+    # selection and compaction at this length: keep 1000 of the ~39 880 candidates
+    cache.keep_idx.fill_(-1)
+    B.dynts_select_evict(cache.ctx, 0, cache.keep_idx, cache.new_len, 1000)
+    keep_same, len_same = orc.select(f64(cache.S[0]), i32(cache.pos[0]), o.seq_len, o.n_prompt, 10, 1000)
+    assert np.array_equal(i32(cache.new_len), len_same) and np.array_equal(i32(cache.keep_idx), keep_same)
+    B.dynts_compact(cache.ctx, 0, cache.keep_idx, cache.new_len)
+    o.compact(keep_same, len_same)
+    n2 = int(len_same[0])
+    assert n2 == M + 1000 + 10 and int(cache.seq_len.item()) == n2
+    assert np.array_equal(f64(cache.K[0])[:, :, :n2], o.K[:, :, :n2]) and np.array_equal(f64(cache.V[0])[:, :, :n2], o.V[:, :, :n2])
+    assert np.array_equal(i32(cache.pos[0])[:, :, :n2], o.pos[:, :, :n2])
