@@ -19,7 +19,8 @@
  *  - Return value: DYNTS_OK or a negative error.  Argument errors are found on the host
  *    before anything is launched.  Conditions only the device can see (a sequence that
  *    would overflow `capacity`) are latched into the bound `status` word: bit 0 = an
- *    append was dropped because the cache was full.
+ *    append was dropped because the cache was full; bit 1 (value 2) = keep_idx too short for a sequence
+ *    (dynts_select_evict left it alone); bit 2 (value 4) = the page pool of the paged layout ran dry.
  *  - Layout (C order, L = n_layers, Nb = batch, Hkv = n_kv_heads, cap = capacity, d = head_dim):
  *      K, V      bf16  [L][Nb][Hkv][cap][d]   rows in position order
  *      S         fp32  [L][Nb][Hkv][cap]      importance score; +inf on question slots
@@ -90,6 +91,22 @@ size_t dynts_workspace_bytes(const dynts_config *cfg);
 int dynts_bind(dynts_ctx *ctx, uint16_t *K, uint16_t *V, float *S, int32_t *pos,
                int32_t *seq_len, int32_t *next_pos, int32_t *n_prompt, void *workspace,
                size_t workspace_bytes, int32_t *status);
+
+/* Paged (block-table) layout instead of one dense [cap][d] array per unit: K_pool, V_pool bf16
+ * [n_pages][64][d] hold the rows of ALL layers, sequences and KV heads; slot j of a unit is row j % 64 of page
+ * block_table[layer][b][h][j / 64] (int32 [L][Nb][Hkv][max_pages], max_pages * 64 >= capacity).  Pages are taken
+ * from and returned to a device-side free stack: free_stack int32 [n_pages] lists page ids, *free_top (device
+ * int32) is the number of free ones (entries [0, *free_top) are free).  The caller initialises the stack (all
+ * pages free: free_stack[i] = i, *free_top = n_pages) and leaves the block table alone; appends and
+ * dynts_prefill pop, dynts_compact gives the pages past the new length back, so evicted memory can be taken by
+ * any other sequence.  dynts_prefill expects the layer's units to hold no pages.  When the stack runs dry the
+ * row is dropped and bit 2 (value 4) of the status word is latched; results are undefined from then on.
+ * S, pos and the per-sequence arrays keep the dense layout.  Everything else behaves as after dynts_bind;
+ * dynts_score_block is not available in this layout (DYNTS_ESHAPE). */
+int dynts_bind_paged(dynts_ctx *ctx, uint16_t *K_pool, uint16_t *V_pool, int32_t n_pages, int32_t *block_table,
+                     int32_t max_pages, int32_t *free_stack, int32_t *free_top, float *S, int32_t *pos,
+                     int32_t *seq_len, int32_t *next_pos, int32_t *n_prompt, void *workspace,
+                     size_t workspace_bytes, int32_t *status);
 
 /* Question window (Sec. 4.2, first paragraph): copy the prompt rows of one layer,
  * K0, V0 bf16 [Nb][Hkv][m_max][d], m int32 [Nb] with m[b] <= m_max, into slots [0, m[b]);

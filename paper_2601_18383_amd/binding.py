@@ -23,7 +23,7 @@ EXPORTS = [
     "dynts_decode_attend_update", "dynts_decode_step", "dynts_select_evict", "dynts_compact",
     "dynts_decode_loop", "dynts_set_kernel_events", "dynts_set_kernel_event_list", "dynts_probe_read_stream",
     "dynts_score_block_scratch_bytes", "dynts_score_block",
-    "dynts_predict_scratch_bytes", "dynts_predict_scores", "dynts_predictor_pack",
+    "dynts_predict_scratch_bytes", "dynts_predict_scores", "dynts_predictor_pack", "dynts_bind_paged",
 ]
 
 
@@ -58,6 +58,7 @@ def _load():
     lib.dynts_workspace_bytes.restype = sz
     lib.dynts_workspace_bytes.argtypes = [C.POINTER(dynts_config)]
     lib.dynts_bind.argtypes = [vp] * 9 + [sz, vp]
+    lib.dynts_bind_paged.argtypes = [vp, vp, vp, i32, vp, i32, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
     lib.dynts_prefill.argtypes = [vp, i32, vp, vp, i32, vp, vp]
     lib.dynts_append.argtypes = [vp, i32, vp, vp, vp, vp, vp]
     lib.dynts_decode_attend.argtypes = [vp, i32, vp, vp, vp, vp, vp]
@@ -149,6 +150,16 @@ def dynts_bind(ctx, K, V, S, pos, seq_len, next_pos, n_prompt, workspace, status
                           _ptr(pos, torch.int32), _ptr(seq_len, torch.int32), _ptr(next_pos, torch.int32),
                           _ptr(n_prompt, torch.int32), _ptr(workspace), workspace.numel() * workspace.element_size(),
                           _ptr(status, torch.int32)), "dynts_bind")
+
+
+def dynts_bind_paged(ctx, K_pool, V_pool, block_table, free_stack, free_top, S, pos, seq_len, next_pos, n_prompt,
+                     workspace, status):
+    _check(lib.dynts_bind_paged(ctx, _ptr(K_pool, torch.bfloat16), _ptr(V_pool, torch.bfloat16), K_pool.shape[0],
+                                _ptr(block_table, torch.int32), block_table.shape[-1], _ptr(free_stack, torch.int32),
+                                _ptr(free_top, torch.int32), _ptr(S, torch.float32), _ptr(pos, torch.int32),
+                                _ptr(seq_len, torch.int32), _ptr(next_pos, torch.int32), _ptr(n_prompt, torch.int32),
+                                _ptr(workspace), workspace.numel() * workspace.element_size(),
+                                _ptr(status, torch.int32)), "dynts_bind_paged")
 
 
 def dynts_prefill(ctx, layer, K0, V0, m, stream=None):
@@ -260,6 +271,77 @@ def dynts_predictor_pack(W, stream=None):
     _check(lib.dynts_predictor_pack(_ptr(W, torch.bfloat16), W.shape[0], W.shape[1], out.data_ptr(), _stream(stream)),
            "dynts_predictor_pack")
     return out
+
+
+PAGE_SLOTS = 64
+
+
+class PagedCache:
+    """The paged layout's buffers (page pools, block table, free stack) allocated with torch and bound.
+    `K` and `V` give a dense [L][Nb][Hkv][cap][d] copy gathered through the block table (for inspection)."""
+
+    def __init__(self, n_layers, batch, n_q_heads, n_kv_heads, head_dim, capacity, budget, window, evict_every,
+                 n_pages=None, softmax_scale=0.0, external_scores=False, device="cuda:0"):
+        self.cfg = make_config(n_layers, batch, n_q_heads, n_kv_heads, head_dim, capacity, budget, window,
+                               evict_every, softmax_scale,
+                               DYNTS_SCORE_EXTERNAL if external_scores else DYNTS_SCORE_ACCUMULATE)
+        self.ctx = dynts_create(self.cfg)
+        dev = torch.device(device)
+        L, Nb, Hkv, cap, d = n_layers, batch, n_kv_heads, capacity, head_dim
+        self.max_pages = (cap + PAGE_SLOTS - 1) // PAGE_SLOTS
+        self.n_pages = L * Nb * Hkv * self.max_pages if n_pages is None else n_pages
+        self.K_pool = torch.zeros((self.n_pages, PAGE_SLOTS, d), dtype=torch.bfloat16, device=dev)
+        self.V_pool = torch.zeros((self.n_pages, PAGE_SLOTS, d), dtype=torch.bfloat16, device=dev)
+        self.block_table = torch.full((L, Nb, Hkv, self.max_pages), -1, dtype=torch.int32, device=dev)
+        self.free_stack = torch.arange(self.n_pages, dtype=torch.int32, device=dev)
+        self.free_top = torch.full((1,), self.n_pages, dtype=torch.int32, device=dev)
+        self.S = torch.zeros((L, Nb, Hkv, cap), dtype=torch.float32, device=dev)
+        self.pos = torch.zeros((L, Nb, Hkv, cap), dtype=torch.int32, device=dev)
+        self.seq_len = torch.zeros((L, Nb), dtype=torch.int32, device=dev)
+        self.next_pos = torch.zeros((L, Nb), dtype=torch.int32, device=dev)
+        self.n_prompt = torch.zeros((Nb,), dtype=torch.int32, device=dev)
+        self.status = torch.zeros((1,), dtype=torch.int32, device=dev)
+        self.workspace = torch.zeros((dynts_workspace_bytes(self.cfg),), dtype=torch.uint8, device=dev)
+        self.keep_idx = torch.zeros((Nb, Hkv, cap), dtype=torch.int32, device=dev)
+        self.new_len = torch.zeros((Nb,), dtype=torch.int32, device=dev)
+        dynts_bind_paged(self.ctx, self.K_pool, self.V_pool, self.block_table, self.free_stack, self.free_top, self.S,
+                         self.pos, self.seq_len, self.next_pos, self.n_prompt, self.workspace, self.status)
+
+    @classmethod
+    def for_workload(cls, wl, device="cuda:0", n_layers=None, n_pages=None):
+        return cls(wl.n_layers if n_layers is None else n_layers, wl.batch, wl.n_q_heads, wl.n_kv_heads,
+                   wl.head_dim, wl.capacity, wl.budget, wl.window, wl.evict_every, n_pages=n_pages,
+                   external_scores=wl.external_scores, device=device)
+
+    def _dense(self, pool):
+        idx = self.block_table.clamp(min=0).long()                      # [L][Nb][Hkv][max_pages]
+        rows = pool[idx]                                                # [...][max_pages][64][d]
+        L, Nb, Hkv, mp = idx.shape
+        return rows.reshape(L, Nb, Hkv, mp * PAGE_SLOTS, pool.shape[-1])[:, :, :, :self.cfg.capacity]
+
+    @property
+    def K(self):
+        return self._dense(self.K_pool)
+
+    @property
+    def V(self):
+        return self._dense(self.V_pool)
+
+    def pages_in_use(self):
+        """Pages the block table should hold for the current lengths, and pages missing from the free stack."""
+        per_unit = (self.seq_len + PAGE_SLOTS - 1) // PAGE_SLOTS        # [L][Nb]
+        return int(per_unit.sum().item()) * self.cfg.n_kv_heads, self.n_pages - int(self.free_top.item())
+
+    def close(self):
+        if self.ctx is not None:
+            dynts_destroy(self.ctx)
+            self.ctx = None
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
 
 
 def dynts_predict_scratch_bytes(w, batch):

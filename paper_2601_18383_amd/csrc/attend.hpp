@@ -69,7 +69,16 @@ struct AttendParams {
   int track;                // 1: scores are accumulated from attention (save q and statistics)
   float scale_log2;         // softmax scale * log2(e)
   unsigned long long *trace;  // timestamps per workgroup (builds with -DDYNTS_TRACE only), else null
+  // paged layout only: K and V are page pools [n_pages][kPageSlots][D]; slot j of a unit lives in page
+  // block_table[unit][j / kPageSlots], row j % kPageSlots
+  const int32_t *block_table;  // layer base, [Nb][Hkv][max_pages]
+  int32_t *block_table_w;      // the same, for the appender
+  int32_t *free_stack;         // [n_pages] page ids; entries below *free_top are free
+  int32_t *free_top;
+  int max_pages, n_pages;
 };
+
+constexpr int kPageSlots = 64;  // slots per page: two tiles, so a tile never straddles pages
 
 #ifdef DYNTS_TRACE
 #define DYNTS_STAMP(slot)                                                                         \
@@ -145,7 +154,7 @@ __device__ __forceinline__ void wave_lds_fence() {
   __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
 }
 
-template <int D, int W, bool ATTEND, bool PENDING, bool APPEND>
+template <int D, int W, bool ATTEND, bool PENDING, bool APPEND, bool PAGED = false>
 __global__ __launch_bounds__(W * 64, 2) void attend_kernel(const AttendParams p) {
   constexpr int kWaves = W, kThreads = W * 64;
   constexpr int KS = D / 32;              // MFMA k-steps per K row
@@ -171,8 +180,26 @@ __global__ __launch_bounds__(W * 64, 2) void attend_kernel(const AttendParams p)
   const int G = p.G;
 
   const size_t unit = (size_t)b * p.Hkv + h;
-  uint16_t *Kb = p.K + unit * (size_t)p.cap * D;
-  uint16_t *Vb = p.V + unit * (size_t)p.cap * D;
+  // dense: this unit's rows; paged: the pools (see paged_base below)
+  uint16_t *Kb = PAGED ? p.K : p.K + unit * (size_t)p.cap * D;
+  uint16_t *Vb = PAGED ? p.V : p.V + unit * (size_t)p.cap * D;
+  const int32_t *tb = PAGED ? p.block_table + unit * (size_t)p.max_pages : nullptr;
+  // Paged addressing of one tile: the tile start is first pulled back into the tile that holds row end-1
+  // (so every clamped row stays in ONE page), then `delta` is the element offset that turns "row r of the
+  // unit" into "row r of that page" for all rows of the tile: address = pool + delta + r * D.
+  auto page_of = [&](int tp) -> int {
+    int pi = tp / kPageSlots;
+    pi = pi < p.max_pages ? pi : p.max_pages - 1;
+    int pg = tb[pi];
+    return pg < 0 ? 0 : (pg >= p.n_pages ? p.n_pages - 1 : pg);  // never followed out of the pool
+  };
+  auto clamp_tile = [&](int tt, int end) -> int {
+    const int last_tile = (end - 1) & ~(kTile - 1);
+    return tt < last_tile ? tt : last_tile;
+  };
+  auto page_delta = [&](int tp, int pg) -> ptrdiff_t {
+    return ((ptrdiff_t)pg * kPageSlots - (ptrdiff_t)(tp & ~(kPageSlots - 1))) * D;
+  };
   float *Sb = p.S + unit * (size_t)p.cap;
   unsigned char *vst = smem + wave * (kTile * VSTRIDE);
   const int vrow_l = lane / PIECES, vpiece = lane % PIECES;
@@ -198,12 +225,12 @@ __global__ __launch_bounds__(W * 64, 2) void attend_kernel(const AttendParams p)
   bf16x8 kf[2][KS];
   u32x4 vf[VIT];
   float s_old = 0.f;
-  load_k_tile<D>(kf, Kb, t, r16, kg, p.cap);
+  if (!PAGED) load_k_tile<D>(kf, Kb, t, r16, kg, p.cap);  // (paged: the page must be looked up first, below)
   if (PENDING) {
     const int tok = t + (lane & (kTile - 1));
     s_old = Sb[tok < p.cap ? tok : p.cap - 1];
   }
-  if (ATTEND) load_v_tile<D>(vf, Vb, t, lane, p.cap);
+  if (ATTEND && !PAGED) load_v_tile<D>(vf, Vb, t, lane, p.cap);
   __builtin_amdgcn_sched_barrier(0);
 
   // query fragments: lane (g, kg) holds q[g][32*ks + 8*kg .. +7]
@@ -312,7 +339,8 @@ __global__ __launch_bounds__(W * 64, 2) void attend_kernel(const AttendParams p)
   }
   // this wave's contiguous range [ra, rb) behind the first tiles
   const int base = kTile * NW;
-  const int per = n_vis > base ? (n_vis - base + NW - 1) / NW : 0;
+  int per = n_vis > base ? (n_vis - base + NW - 1) / NW : 0;
+  if (PAGED) per = (per + kTile - 1) & ~(kTile - 1);  // whole tiles, so that no tile straddles two pages
   const int ra = base + wi * per;
   const int rb = ra + per < n_vis ? ra + per : n_vis;
 
@@ -345,11 +373,36 @@ __global__ __launch_bounds__(W * 64, 2) void attend_kernel(const AttendParams p)
       const bf16x4 v4 = __builtin_bit_cast(bf16x4, vn[cb]);
       oacc[cb] = f32x4{(float)v4[0], (float)v4[1], (float)v4[2], (float)v4[3]};
     }
-    if (r16 == 0) {
+    size_t new_row = (size_t)n_old * D;  // element offset of the new row from Kb / Vb
+    bool have_row = true;
+    if (PAGED) {
+      // the slot's page: a fresh one from the free stack when the slot opens a page
+      int pg = 0;
+      if (lane == 0) {
+        const int pi = n_old / kPageSlots;
+        if (n_old % kPageSlots == 0) {
+          const int idx = atomicSub(p.free_top, 1) - 1;
+          if (idx >= 0) {
+            pg = p.free_stack[idx];
+            p.block_table_w[unit * (size_t)p.max_pages + pi] = pg;
+          } else {  // pool exhausted: give the ticket back, drop the row, say so
+            atomicAdd(p.free_top, 1);
+            atomicOr(p.status, 4);
+            pg = -1;
+          }
+        } else {
+          pg = tb[pi];
+        }
+      }
+      pg = __builtin_amdgcn_readfirstlane(pg);
+      have_row = pg >= 0 && pg < p.n_pages;
+      new_row = ((size_t)(have_row ? pg : 0) * kPageSlots + n_old % kPageSlots) * D;
+    }
+    if (r16 == 0 && have_row) {
 #pragma unroll
-      for (int cb = 0; cb < CB; ++cb) *reinterpret_cast<uint2 *>(Vb + (size_t)n_old * D + 16 * cb + 4 * kg) = vn[cb];
+      for (int cb = 0; cb < CB; ++cb) *reinterpret_cast<uint2 *>(Vb + new_row + 16 * cb + 4 * kg) = vn[cb];
 #pragma unroll
-      for (int ks = 0; ks < KS; ++ks) store_bf16x8(Kb + (size_t)n_old * D + 32 * ks + 8 * kg, kn[ks]);
+      for (int ks = 0; ks < KS; ++ks) store_bf16x8(Kb + new_row + 32 * ks + 8 * kg, kn[ks]);
     }
     if (lane == 0) {
       Sb[n_old] = s_init;
@@ -360,7 +413,7 @@ __global__ __launch_bounds__(W * 64, 2) void attend_kernel(const AttendParams p)
   seq_checkin();
 
   // the first tile was fetched before the length was known: keep rows past the sequence out of P.V
-  if (ATTEND && t + kTile > n_rows) {
+  if (ATTEND && !PAGED && t + kTile > n_rows) {
 #pragma unroll
     for (int it = 0; it < VIT; ++it) vf[it] = (t + VROWS * it + vrow_l < n_rows) ? vf[it] : u32x4{0u, 0u, 0u, 0u};
   }
@@ -370,7 +423,19 @@ __global__ __launch_bounds__(W * 64, 2) void attend_kernel(const AttendParams p)
   const int own_end = ra < rb ? rb : (t + kTile < n_vis ? t + kTile : n_vis);
   const int k_last = own_end > 0 ? own_end : 1;
   const int v_end = own_end < n_rows ? own_end : n_rows;
-  const int v_last = v_end > 0 ? v_end : 1;
+  // (paged: V rows are clamped like K rows, so that one page serves both; slots below n_vis are allocated,
+  // and whatever lies past n_rows meets a zero weight)
+  const int v_last = PAGED ? k_last : (v_end > 0 ? v_end : 1);
+  // paged: the page of the next tile to fetch is looked up one tile ahead of its use
+  int pg_nxt = 0;
+  if (PAGED) {
+    const int tp0 = clamp_tile(t, k_last), tp1 = clamp_tile(ra, k_last);
+    const int pg0 = page_of(tp0);
+    pg_nxt = page_of(tp1);
+    const ptrdiff_t d0 = page_delta(tp0, pg0);
+    load_k_tile<D>(kf, Kb + d0, tp0, r16, kg, k_last);
+    if (ATTEND) load_v_tile<D>(vf, Vb + d0, tp0, lane, v_last);
+  }
 
   // ---- one 32-slot tile of this wave -------------------------------------------------------
   // Branch-free apart from two wave-uniform guards; the next tile's loads are issued
@@ -395,7 +460,14 @@ __global__ __launch_bounds__(W * 64, 2) void attend_kernel(const AttendParams p)
       }
     }
     const float s_cur = s_old;
-    load_k_tile<D>(kf, Kb, tn, r16, kg, k_last);
+    ptrdiff_t dn = 0;   // paged: element offset of the next tile's page, and its clamped start
+    int tnp = tn;
+    if (PAGED) {
+      tnp = clamp_tile(tn, k_last);
+      dn = page_delta(tnp, pg_nxt);
+      pg_nxt = page_of(clamp_tile(tn + kTile, k_last));
+    }
+    load_k_tile<D>(kf, Kb + dn, tnp, r16, kg, k_last);
     if (PENDING) {
       const int tok = tn + (lane & (kTile - 1));
       s_old = Sb[tok < p.cap ? tok : p.cap - 1];
@@ -465,7 +537,7 @@ __global__ __launch_bounds__(W * 64, 2) void attend_kernel(const AttendParams p)
       for (int it = 0; it < VIT; ++it)
         *reinterpret_cast<u32x4 *>(vst + (VROWS * it + vrow_l) * VSTRIDE + 16 * vpiece) = vf[it];
       wave_lds_fence();
-      load_v_tile<D>(vf, Vb, tn, lane, v_last);
+      load_v_tile<D>(vf, Vb + dn, tnp, lane, v_last);
 #pragma unroll
       for (int cb = 0; cb < CB; ++cb) {
         // V^T operand: lane (c = 16 cb + r16, kg) gets V[t + 16 s + 4 kg + i][c] as element 4 s + i.

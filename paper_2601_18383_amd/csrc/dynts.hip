@@ -13,6 +13,7 @@
 
 #include "attend.hpp"
 #include "compact.hpp"
+#include "paged.hpp"
 #include "predictor.hpp"
 #include "probe.hpp"
 #include "score_block.hpp"
@@ -104,6 +105,10 @@ struct dynts_ctx {
   std::vector<hipEvent_t> ev_list_start, ev_list_stop;  // one pair per coming attend launch
   size_t ev_list_next = 0;
   unsigned long long *trace = nullptr;
+  // paged layout (dynts_bind_paged): K and V above are the page pools
+  bool paged = false;
+  int32_t *block_table = nullptr, *free_stack = nullptr, *free_top = nullptr;
+  int max_pages = 0, n_pages = 0;
 };
 
 namespace {
@@ -124,6 +129,7 @@ struct LayerView {
   uint16_t *qprev, *qnext;
   float *mlprev;
   int32_t *nprev;
+  int32_t *block_table;  // paged layout: this layer's [Nb][Hkv][max_pages]
 };
 
 LayerView layer_view(const dynts_ctx *ctx, int layer) {
@@ -131,8 +137,9 @@ LayerView layer_view(const dynts_ctx *ctx, int layer) {
   const size_t units = (size_t)c.batch * c.n_kv_heads;
   const size_t rows = units * c.capacity;
   LayerView v;
-  v.K = ctx->K + (size_t)layer * rows * c.head_dim;
-  v.V = ctx->V + (size_t)layer * rows * c.head_dim;
+  v.K = ctx->paged ? ctx->K : ctx->K + (size_t)layer * rows * c.head_dim;
+  v.V = ctx->paged ? ctx->V : ctx->V + (size_t)layer * rows * c.head_dim;
+  v.block_table = ctx->paged ? ctx->block_table + (size_t)layer * units * ctx->max_pages : nullptr;
   v.S = ctx->S + (size_t)layer * rows;
   v.pos = ctx->pos + (size_t)layer * rows;
   v.seq_len = ctx->seq_len + (size_t)layer * c.batch;
@@ -151,8 +158,12 @@ LayerView layer_view(const dynts_ctx *ctx, int layer) {
 // kernel's own begin and end
 template <int D, int W, bool ATTEND, bool PENDING, bool APPEND>
 void launch_partial(const dynts::AttendParams &p, dim3 grid, hipStream_t st, hipEvent_t start, hipEvent_t stop) {
-  hipExtLaunchKernelGGL((dynts::attend_kernel<D, W, ATTEND, PENDING, APPEND>), grid, dim3(W * 64), 0, st, start, stop,
-                        0, p);
+  if (p.block_table)
+    hipExtLaunchKernelGGL((dynts::attend_kernel<D, W, ATTEND, PENDING, APPEND, true>), grid, dim3(W * 64), 0, st, start,
+                          stop, 0, p);
+  else
+    hipExtLaunchKernelGGL((dynts::attend_kernel<D, W, ATTEND, PENDING, APPEND, false>), grid, dim3(W * 64), 0, st, start,
+                          stop, 0, p);
 }
 
 template <int D, int W>
@@ -190,6 +201,8 @@ int run_attend(dynts_ctx *ctx, int layer, const uint16_t *q, const uint16_t *k_n
   p.Nb = c.batch; p.Hq = c.n_q_heads; p.Hkv = c.n_kv_heads; p.G = pl.G; p.cap = c.capacity;
   p.chunk = pl.chunk; p.nsplit = pl.nsplit; p.track = track ? 1 : 0; p.scale_log2 = ctx->scale_log2;
   p.trace = ctx->trace;
+  p.block_table = lv.block_table; p.block_table_w = lv.block_table; p.free_stack = ctx->free_stack;
+  p.free_top = ctx->free_top; p.max_pages = ctx->max_pages; p.n_pages = ctx->n_pages;
 
   const dim3 grid(pl.nsplit, c.n_kv_heads, c.batch);
   hipEvent_t e0 = ctx->ev_start, e1 = ctx->ev_stop;
@@ -326,9 +339,25 @@ int dynts_bind(dynts_ctx *ctx, uint16_t *K, uint16_t *V, float *S, int32_t *pos,
   if ((reinterpret_cast<uintptr_t>(K) | reinterpret_cast<uintptr_t>(V)) % 16) return DYNTS_EINVAL;
   ctx->K = K; ctx->V = V; ctx->S = S; ctx->pos = pos; ctx->seq_len = seq_len; ctx->next_pos = next_pos;
   ctx->n_prompt = n_prompt; ctx->ws = static_cast<unsigned char *>(workspace); ctx->status = status;
+  ctx->paged = false; ctx->block_table = nullptr; ctx->free_stack = nullptr; ctx->free_top = nullptr;
+  ctx->max_pages = ctx->n_pages = 0;
   ctx->pending.assign(ctx->pending.size(), 0);
   ctx->qslot.assign(ctx->qslot.size(), 0);
   ctx->bound = true;
+  return DYNTS_OK;
+}
+
+int dynts_bind_paged(dynts_ctx *ctx, uint16_t *K_pool, uint16_t *V_pool, int32_t n_pages, int32_t *block_table,
+                     int32_t max_pages, int32_t *free_stack, int32_t *free_top, float *S, int32_t *pos,
+                     int32_t *seq_len, int32_t *next_pos, int32_t *n_prompt, void *workspace, size_t workspace_bytes,
+                     int32_t *status) {
+  if (!ctx || !block_table || !free_stack || !free_top) return DYNTS_ENULL;
+  if (n_pages <= 0 || max_pages <= 0) return DYNTS_EINVAL;
+  if ((long long)max_pages * dynts::kPageSlots < ctx->cfg.capacity) return DYNTS_ECAPACITY;
+  const int rc = dynts_bind(ctx, K_pool, V_pool, S, pos, seq_len, next_pos, n_prompt, workspace, workspace_bytes, status);
+  if (rc != DYNTS_OK) return rc;
+  ctx->paged = true; ctx->block_table = block_table; ctx->free_stack = free_stack; ctx->free_top = free_top;
+  ctx->max_pages = max_pages; ctx->n_pages = n_pages;
   return DYNTS_OK;
 }
 
@@ -347,8 +376,18 @@ int dynts_prefill(dynts_ctx *ctx, int32_t layer, const uint16_t *K0, const uint1
   const int rows = 256 / (c.head_dim / 8);
   const dim3 grid((m_max + rows - 1) / rows, c.n_kv_heads, c.batch);
   hipStream_t st = static_cast<hipStream_t>(stream);
-  if (c.head_dim == 128) hipLaunchKernelGGL((dynts::prefill_kernel<128>), grid, dim3(256), 0, st, p);
-  else hipLaunchKernelGGL((dynts::prefill_kernel<64>), grid, dim3(256), 0, st, p);
+  if (ctx->paged) {
+    const dynts::PagedView pv{lv.K, lv.V, lv.block_table, ctx->free_stack, ctx->free_top, ctx->max_pages, ctx->n_pages};
+    const int units = c.batch * c.n_kv_heads;
+    hipLaunchKernelGGL(dynts::paged_alloc_kernel, dim3((units + 63) / 64), dim3(64), 0, st, pv, nullptr, m, m_max,
+                       c.batch, c.n_kv_heads, ctx->status);
+    if (c.head_dim == 128) hipLaunchKernelGGL((dynts::paged_prefill_kernel<128>), grid, dim3(256), 0, st, p, pv);
+    else hipLaunchKernelGGL((dynts::paged_prefill_kernel<64>), grid, dim3(256), 0, st, p, pv);
+  } else if (c.head_dim == 128) {
+    hipLaunchKernelGGL((dynts::prefill_kernel<128>), grid, dim3(256), 0, st, p);
+  } else {
+    hipLaunchKernelGGL((dynts::prefill_kernel<64>), grid, dim3(256), 0, st, p);
+  }
   ctx->pending[layer] = 0;
   return launch_status();
 }
@@ -367,8 +406,15 @@ int dynts_append(dynts_ctx *ctx, int32_t layer, const uint16_t *k_new, const uin
                         c.n_kv_heads, c.capacity};
   const int threads = (c.n_kv_heads * (c.head_dim / 8) + 63) / 64 * 64;
   hipStream_t st = static_cast<hipStream_t>(stream);
-  if (c.head_dim == 128) hipLaunchKernelGGL((dynts::append_kernel<128>), dim3(c.batch), dim3(threads), 0, st, p);
-  else hipLaunchKernelGGL((dynts::append_kernel<64>), dim3(c.batch), dim3(threads), 0, st, p);
+  if (ctx->paged) {
+    const dynts::PagedView pv{lv.K, lv.V, lv.block_table, ctx->free_stack, ctx->free_top, ctx->max_pages, ctx->n_pages};
+    if (c.head_dim == 128) hipLaunchKernelGGL((dynts::paged_append_kernel<128>), dim3(c.batch), dim3(threads), 0, st, p, pv);
+    else hipLaunchKernelGGL((dynts::paged_append_kernel<64>), dim3(c.batch), dim3(threads), 0, st, p, pv);
+  } else if (c.head_dim == 128) {
+    hipLaunchKernelGGL((dynts::append_kernel<128>), dim3(c.batch), dim3(threads), 0, st, p);
+  } else {
+    hipLaunchKernelGGL((dynts::append_kernel<64>), dim3(c.batch), dim3(threads), 0, st, p);
+  }
   return launch_status();
 }
 
@@ -457,8 +503,17 @@ int dynts_compact(dynts_ctx *ctx, int32_t layer, const uint8_t *trigger, const i
                          c.n_kv_heads, c.capacity, keep_stride};
   const dim3 grid(2 * (c.head_dim * 2 / 64) + 2, c.n_kv_heads, c.batch);
   hipStream_t st = static_cast<hipStream_t>(stream);
-  if (c.head_dim == 128) hipLaunchKernelGGL((dynts::compact_kernel<128>), grid, dim3(dynts::kCompactThreads), 0, st, p);
-  else hipLaunchKernelGGL((dynts::compact_kernel<64>), grid, dim3(dynts::kCompactThreads), 0, st, p);
+  if (ctx->paged) {
+    const dynts::PagedView pv{lv.K, lv.V, lv.block_table, ctx->free_stack, ctx->free_top, ctx->max_pages, ctx->n_pages};
+    if (c.head_dim == 128) hipLaunchKernelGGL((dynts::paged_compact_kernel<128>), grid, dim3(dynts::kCompactThreads), 0, st, p, pv);
+    else hipLaunchKernelGGL((dynts::paged_compact_kernel<64>), grid, dim3(dynts::kCompactThreads), 0, st, p, pv);
+    hipLaunchKernelGGL(dynts::paged_trim_kernel, dim3((c.batch + 63) / 64), dim3(64), 0, st, pv, trigger, new_len,
+                       lv.seq_len, c.batch, c.n_kv_heads, c.capacity, keep_stride);
+  } else if (c.head_dim == 128) {
+    hipLaunchKernelGGL((dynts::compact_kernel<128>), grid, dim3(dynts::kCompactThreads), 0, st, p);
+  } else {
+    hipLaunchKernelGGL((dynts::compact_kernel<64>), grid, dim3(dynts::kCompactThreads), 0, st, p);
+  }
   return launch_status();
 }
 
@@ -506,6 +561,7 @@ int dynts_score_block(dynts_ctx *ctx, int32_t layer, const uint16_t *q_blk, cons
   int rc = check_call(ctx, layer);
   if (rc != DYNTS_OK) return rc;
   if (!q_blk || !scratch) return DYNTS_ENULL;
+  if (ctx->paged) return DYNTS_ESHAPE;  // block scoring reads the dense layout only
   if (n_queries <= 0 || n_queries > (1 << 20)) return DYNTS_EINVAL;
   if (reinterpret_cast<uintptr_t>(q_blk) % 16 || reinterpret_cast<uintptr_t>(k_blk) % 16) return DYNTS_EINVAL;
   const dynts_config &c = ctx->cfg;

@@ -1,0 +1,143 @@
+"""GPU parity of the paged (block-table) cache layout: the same decode path, K/V rows found through a page
+table, pages popped on append and pushed back after compaction.  Compared with the float64 oracle through a
+dense view gathered from the pools."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import dynts_oracle as orc
+from paper_2601_18383_amd import configs, synth
+from tests.helpers import SideBySide, assert_close, f64, i32
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def B():
+    from paper_2601_18383_amd import binding
+    return binding
+
+
+def _bf16(rng, *shape, scale=1.0):
+    return torch.from_numpy(rng.standard_normal(shape).astype(np.float32) * scale).to(torch.bfloat16)
+
+
+def _check_pages(cache):
+    """Every page is either free or held by exactly one unit; the units hold what their lengths need."""
+    need, missing = cache.pages_in_use()
+    assert need == missing, (need, missing)
+    top = int(cache.free_top.item())
+    free = i32(cache.free_stack)[:top].tolist()
+    L, Nb = cache.seq_len.shape
+    held = []
+    bt, sl = i32(cache.block_table), i32(cache.seq_len)
+    for l in range(L):
+        for b in range(Nb):
+            for h in range(cache.cfg.n_kv_heads):
+                held += bt[l, b, h, :(sl[l, b] + 63) // 64].tolist()
+    assert len(set(held)) == len(held) and not (set(held) & set(free)) and len(set(free)) == len(free)
+    assert sorted(held + free) == list(range(cache.n_pages))
+
+
+@pytest.mark.parametrize("one_workgroup", [False, True])
+@pytest.mark.parametrize("mode", ["unfused", "fused", "step"])
+@pytest.mark.parametrize("d,Hq,Hkv", [(64, 8, 2), (128, 28, 4)])
+def test_trajectory_paged(B, mode, d, Hq, Hkv, one_workgroup, monkeypatch):
+    """Several pages per unit, ragged prompts, evictions that free pages, a sequence that finishes early.
+    one_workgroup: a single workgroup per unit, so that every wave walks a range of tiles behind its first one
+    (the launch shape of the large workloads) instead of one tile each."""
+    if one_workgroup:
+        monkeypatch.setenv("DYNTS_TARGET_WGS", "1")
+    rng = np.random.default_rng(300 + d + Hq)
+    Nb, M_max, budget, window, E, T = 3, 37, 150, 19, 91, 420
+    cap = M_max + budget + window + E
+    cache = B.PagedCache(1, Nb, Hq, Hkv, d, cap, budget, window, E)
+    o = orc.OracleLayer(Nb, Hq, Hkv, d, cap, budget, window, E)
+    sbs = SideBySide(B, cache, 0, o, mode)
+    sbs.prefill(_bf16(rng, Nb, Hkv, M_max, d), _bf16(rng, Nb, Hkv, M_max, d), [37, 5, 20])
+    _check_pages(cache)
+    last = [T, 130, T]
+    for t in range(1, T + 1):
+        active = np.array([t <= last[b] for b in range(Nb)], np.uint8)
+        trig = sbs.step(_bf16(rng, Nb, Hq, d, scale=1.5), _bf16(rng, Nb, Hkv, d), _bf16(rng, Nb, Hkv, d), active=active,
+                        check_scores=(t % 7 == 0 or mode == "unfused"))
+        if trig.any() or t % 50 == 0:
+            _check_pages(cache)
+    sbs.check_scores()
+    sbs.check_state()
+    assert sbs.evictions >= 2 and int(cache.status.item()) == 0
+    assert int(cache.seq_len[0, 1].item()) == sbs.o.seq_len[1]
+
+
+def test_pool_shared_between_sequences_and_exhaustion(B):
+    """A pool smaller than batch x capacity: eviction returns pages that other sequences then take; when the pool
+    runs dry the status word says so."""
+    rng = np.random.default_rng(41)
+    dev = torch.device("cuda:0")
+    Nb, Hq, Hkv, d = 4, 8, 2, 64
+    M, budget, window, E = 10, 64, 20, 108          # capacity 202 slots = 4 pages per unit
+    cap = M + budget + window + E
+    n_pages = Nb * Hkv * 3 + 2                      # not enough for everyone at full length (would be 32)
+    cache = B.PagedCache(1, Nb, Hq, Hkv, d, cap, budget, window, E, n_pages=n_pages)
+    o = orc.OracleLayer(Nb, Hq, Hkv, d, cap, budget, window, E)
+    sbs = SideBySide(B, cache, 0, o, "step")
+    sbs.prefill(_bf16(rng, Nb, Hkv, M, d), _bf16(rng, Nb, Hkv, M, d), [M] * Nb)
+    # 180 steps: every unit needs 3 pages (190 slots), the pool has 26
+    for t in range(1, 181):
+        sbs.step(_bf16(rng, Nb, Hq, d), _bf16(rng, Nb, Hkv, d), _bf16(rng, Nb, Hkv, d), check_scores=False)
+    assert int(cache.status.item()) == 0
+    _check_pages(cache)
+    assert int(cache.free_top.item()) == 2
+    # step 182 fills the cache (10 + 192 = 202) only after a 4th page: 8 units want one, 2 are left -> exhaustion
+    q, k, v = _bf16(rng, Nb, Hq, d), _bf16(rng, Nb, Hkv, d), _bf16(rng, Nb, Hkv, d)
+    for t in range(181, 184):
+        B.dynts_decode_step(cache.ctx, 0, q.to(dev), k.to(dev), v.to(dev), sbs.out)
+    assert int(cache.status.item()) & 4
+    assert int(cache.free_top.item()) == 0
+
+
+def test_cfg3_full_shape_paged(B):
+    """cfg3 at full shape through the paged layout: steady state reached by the path itself, sampled sequences
+    against the oracle replaying the same steps from a snapshot."""
+    wl = configs.get("cfg3")
+    dev = torch.device("cuda:0")
+    gen = synth.Synth(wl, dev)
+    cache = B.PagedCache.for_workload(wl, device=dev)
+    K0, V0 = gen.prompt_kv(0)
+    B.dynts_prefill(cache.ctx, 0, K0, V0, torch.full((wl.batch,), wl.prompt, dtype=torch.int32, device=dev))
+    out = torch.zeros((1, wl.batch, wl.n_q_heads, wl.head_dim), dtype=torch.float32, device=dev)
+    T0 = wl.budget + wl.window + wl.evict_every + 5       # just past the first eviction
+    steps = torch.arange(1, T0 + 1)
+    q = gen.q(0, steps).unsqueeze(1).contiguous()
+    k, v = gen.kv(0, steps)
+    k, v = k.unsqueeze(1).contiguous(), v.unsqueeze(1).contiguous()
+    flags = torch.zeros(T0, dtype=torch.uint8)
+    flags[wl.budget + wl.window + wl.evict_every - 1] = 1
+    B.dynts_decode_loop(cache.ctx, T0, q, k, v, out, cache.keep_idx, cache.new_len, evict_steps=flags)
+    B.dynts_update_scores(cache.ctx, 0)
+    assert int(cache.status.item()) == 0
+    n0 = wl.steady_len + 5
+    assert np.all(i32(cache.seq_len[0]) == n0)
+    _check_pages(cache)
+    # snapshot -> oracle, then three more fused steps on both
+    sample = [0, 17]
+    o = orc.OracleLayer(len(sample), wl.n_q_heads, wl.n_kv_heads, wl.head_dim, wl.capacity, wl.budget, wl.window,
+                        wl.evict_every)
+    Kd, Vd = cache.K[0][sample], cache.V[0][sample]
+    o.K[:, :, :n0] = f64(Kd[:, :, :n0]); o.V[:, :, :n0] = f64(Vd[:, :, :n0])
+    o.S[:, :, :n0] = f64(cache.S[0][sample][:, :, :n0]); o.pos[:, :, :n0] = i32(cache.pos[0][sample][:, :, :n0])
+    o.seq_len[:] = n0; o.n_prompt[:] = wl.prompt; o.next_pos[:] = i32(cache.next_pos[0][sample])
+    steps2 = torch.arange(T0 + 1, T0 + 4)
+    q2 = gen.q(0, steps2); k2, v2 = gen.kv(0, steps2)
+    o1 = torch.zeros((wl.batch, wl.n_q_heads, wl.head_dim), dtype=torch.float32, device=dev)
+    for i in range(3):
+        B.dynts_decode_step(cache.ctx, 0, q2[i], k2[i], v2[i], o1)
+        o.append(f64(k2[i][sample]), f64(v2[i][sample]))
+        ref, alpha, _ = o.attend(f64(q2[i][sample]))
+        o.update_scores(alpha)
+        assert_close(f64(o1[sample]), ref, "paged cfg3 out, step %d" % i)
+    B.dynts_update_scores(cache.ctx, 0)
+    n1 = n0 + 3
+    assert_close(f64(cache.S[0][sample][:, :, :n1]), o.S[:, :, :n1], "paged cfg3 S")
+    assert np.array_equal(f64(cache.K[0][sample][:, :, :n1]), o.K[:, :, :n1])
+    cache.close()

@@ -53,6 +53,25 @@ def test_trajectory_small(B, mode, d, Hq, Hkv):
     assert int(sbs.c.seq_len[0, 1].item()) == sbs.o.seq_len[1]
 
 
+@pytest.mark.parametrize("waves", ["4", "8"])
+@pytest.mark.parametrize("d,Hq,Hkv", [(64, 8, 2), (128, 28, 4)])
+def test_trajectory_single_workgroup(B, d, Hq, Hkv, waves, monkeypatch):
+    """One workgroup per (sequence, KV head), 4 or 8 waves: every wave walks a ragged range of slots behind its
+    first tile, the launch shape of the large workloads, here at a size the oracle replays step by step."""
+    monkeypatch.setenv("DYNTS_TARGET_WGS", "1")
+    monkeypatch.setenv("DYNTS_WAVES", waves)
+    rng = np.random.default_rng(500 + d + Hq)
+    Nb, M_max, budget, window, E, T = 2, 41, 330, 23, 57, 560
+    sbs, cap = _pair(B, Nb, Hq, Hkv, d, M_max, budget, window, E, "step")
+    sbs.prefill(_bf16(rng, Nb, Hkv, M_max, d), _bf16(rng, Nb, Hkv, M_max, d), [41, 7])
+    for t in range(1, T + 1):
+        sbs.step(_bf16(rng, Nb, Hq, d, scale=1.5), _bf16(rng, Nb, Hkv, d), _bf16(rng, Nb, Hkv, d),
+                 check_scores=(t % 11 == 0))
+    sbs.check_scores()
+    sbs.check_state()
+    assert sbs.evictions >= 3 and int(sbs.c.status.item()) == 0
+
+
 @pytest.mark.parametrize("mode", ["fused", "step"])
 def test_trajectory_paper_shaped_schedule(B, mode):
     """The paper's own budget shape (Sec. 6.1, inference settings) in small: a wide local window, and a
