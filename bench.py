@@ -148,7 +148,7 @@ def run_gpu(args, wl):
     props = torch.cuda.get_device_properties(0)
     log("device: %s, %d CUs, %.0f GiB" % (props.name, props.multi_processor_count, props.total_memory / 2 ** 30))
     gen = synth.Synth(wl, dev)
-    cache = B.Cache.for_workload(wl, device=dev)
+    cache = (B.PagedCache if args.paged else B.Cache).for_workload(wl, device=dev)
     L = wl.n_layers
     for l in range(L):
         K0, V0 = gen.prompt_kv(l)
@@ -264,7 +264,7 @@ def run_trajectory(args, wl):
 
     dev = torch.device("cuda:0")
     gen = synth.Synth(wl, dev)
-    cache = B.Cache.for_workload(wl, device=dev)
+    cache = (B.PagedCache if args.paged else B.Cache).for_workload(wl, device=dev)
     L = wl.n_layers
     for l in range(L):
         K0, V0 = gen.prompt_kv(l)
@@ -474,7 +474,8 @@ def result_line(args, wl, r, cpu):
                                 r["mode"] if "mode" in r else
                                 "block scoring of %d queries per sequence on a steady-state cache" % args.score_block
                                 if getattr(args, "score_block", 0) else
-                                "whole decode from the prompt" if args.trajectory else "steady state",
+                                "whole decode from the prompt" if args.trajectory else
+                                "steady state, paged layout" if getattr(args, "paged", False) else "steady state",
                                 r["active_min"], r["active_max"], wl.batch),
                    "first_timed_step": r["first_timed_step"], "evictions_in_window": r["evictions_timed"],
                    "sequence_steps_per_s": round(r["seq_steps_per_s"], 1), "timed_windows": r.get("windows"),
@@ -500,6 +501,8 @@ def main():
     ap.add_argument("--score-block", type=int, default=0, metavar="T",
                     help="time dynts_score_block for a block of T queries (with their keys) on a steady-state "
                          "cache instead of the decode path")
+    ap.add_argument("--paged", action="store_true",
+                    help="steady-state run on the paged (block-table) cache layout instead of the dense one")
     ap.add_argument("--predictor", action="store_true",
                     help="time the Importance Predictor head (synthetic weights at the workload's model size)")
     ap.add_argument("--full-kv", action="store_true",
