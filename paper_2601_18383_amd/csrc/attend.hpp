@@ -41,7 +41,7 @@ typedef short i16x8 __attribute__((ext_vector_type(8)));
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 
 constexpr int kTile = 32;           // cache slots one wave handles per iteration
-// A workgroup has W waves (4 or 8); chunk sizes are multiples of W * kTile slots.
+// A workgroup has W waves (4 or 8).
 
 struct AttendParams {
   uint16_t *K, *V;          // layer base, [Nb][Hkv][cap][D]
@@ -65,7 +65,7 @@ struct AttendParams {
   uint32_t *unit_cnt;       // [Nb][Hkv] arrival counters, zero between launches
   uint32_t *seq_cnt;        // [Nb]      arrival counters, zero between launches
   int32_t *status;
-  int Nb, Hq, Hkv, G, cap, chunk, nsplit;
+  int Nb, Hq, Hkv, G, cap, nsplit;
   int track;                // 1: scores are accumulated from attention (save q and statistics)
   float scale_log2;         // softmax scale * log2(e)
   unsigned long long *trace;  // timestamps per workgroup (builds with -DDYNTS_TRACE only), else null

@@ -199,7 +199,7 @@ int run_attend(dynts_ctx *ctx, int layer, const uint16_t *q, const uint16_t *k_n
   p.seq_cnt = reinterpret_cast<uint32_t *>(ctx->ws + pl.off_seq_cnt);
   p.status = ctx->status;
   p.Nb = c.batch; p.Hq = c.n_q_heads; p.Hkv = c.n_kv_heads; p.G = pl.G; p.cap = c.capacity;
-  p.chunk = pl.chunk; p.nsplit = pl.nsplit; p.track = track ? 1 : 0; p.scale_log2 = ctx->scale_log2;
+  p.nsplit = pl.nsplit; p.track = track ? 1 : 0; p.scale_log2 = ctx->scale_log2;
   p.trace = ctx->trace;
   p.block_table = lv.block_table; p.block_table_w = lv.block_table; p.free_stack = ctx->free_stack;
   p.free_top = ctx->free_top; p.max_pages = ctx->max_pages; p.n_pages = ctx->n_pages;

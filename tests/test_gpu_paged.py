@@ -141,3 +141,29 @@ def test_cfg3_full_shape_paged(B):
     assert_close(f64(cache.S[0][sample][:, :, :n1]), o.S[:, :, :n1], "paged cfg3 S")
     assert np.array_equal(f64(cache.K[0][sample][:, :, :n1]), o.K[:, :, :n1])
     cache.close()
+
+
+def test_two_layers_share_one_pool(B):
+    """Two layers with different inputs draw from and return to the same pool."""
+    rng = np.random.default_rng(43)
+    Nb, Hq, Hkv, d = 2, 8, 2, 64
+    M, budget, window, E = 9, 70, 11, 75
+    cap = M + budget + window + E
+    cache = B.PagedCache(2, Nb, Hq, Hkv, d, cap, budget, window, E, n_pages=2 * Nb * Hkv * 3)
+    layers = []
+    for l in range(2):
+        o = orc.OracleLayer(Nb, Hq, Hkv, d, cap, budget, window, E)
+        sbs = SideBySide(B, cache, l, o, "step")
+        sbs.prefill(_bf16(rng, Nb, Hkv, M, d), _bf16(rng, Nb, Hkv, M, d), [M, 4])
+        layers.append(sbs)
+    for t in range(1, 2 * E + budget + window + 3):
+        for sbs in layers:
+            sbs.step(_bf16(rng, Nb, Hq, d), _bf16(rng, Nb, Hkv, d), _bf16(rng, Nb, Hkv, d), check_scores=(t % 13 == 0))
+        if t % 40 == 0:
+            _check_pages(cache)
+    for sbs in layers:
+        sbs.check_scores()
+        sbs.check_state()
+        assert sbs.evictions == 2
+    _check_pages(cache)
+    assert int(cache.status.item()) == 0
