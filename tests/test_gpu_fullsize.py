@@ -203,3 +203,46 @@ def test_ragged_batch_full_shape(B):
         assert_close(S_gpu[bi, :, :n], o.S[bi, :, :n], "ragged S")
         assert np.array_equal(i32(cache.pos[0][sample][bi, :, :n]), o.pos[bi, :, :n])
     assert int(cache.status.item()) == 0
+
+
+def test_results_are_reproducible_bit_for_bit_and_stream_independent(B):
+    """The same steps from the same state give the same bits (partials are merged in index order, every score has
+    one owner), on the null stream and on a stream of the caller's own."""
+    wl = configs.get("cfg3")
+    dev = torch.device("cuda:0")
+    gen = synth.Synth(wl, dev)
+    n0 = wl.steady_len + 40
+    st = gen.steady_state(0, n0)
+    T = wl.evict_every - 40 + 3           # runs through one trigger
+    steps = torch.arange(9000, 9000 + T)
+    q = gen.q(0, steps).unsqueeze(1).contiguous()
+    k, v = gen.kv(0, steps)
+    k, v = k.unsqueeze(1).contiguous(), v.unsqueeze(1).contiguous()
+    flags = torch.zeros(T, dtype=torch.uint8)
+    flags[wl.evict_every - 40 - 1] = 1
+    results = []
+    for use_stream in (None, None, torch.cuda.Stream()):
+        cache = B.Cache.for_workload(wl, device=dev)
+        cache.K[0, :, :, :n0] = st["K"]; cache.V[0, :, :, :n0] = st["V"]
+        cache.S[0, :, :, :n0] = st["S"]; cache.pos[0, :, :, :n0] = st["pos"]
+        cache.seq_len[0].fill_(n0); cache.next_pos[0].fill_(10 ** 6); cache.n_prompt.fill_(wl.prompt)
+        outs = torch.zeros((T, 1, wl.batch, wl.n_q_heads, wl.head_dim), dtype=torch.float32, device=dev)
+        torch.cuda.synchronize()
+        if use_stream is None:
+            B.dynts_decode_loop(cache.ctx, T, q, k, v, outs, cache.keep_idx, cache.new_len, evict_steps=flags,
+                                out_step_stride=outs[0].numel())
+            B.dynts_update_scores(cache.ctx, 0)
+        else:
+            with torch.cuda.stream(use_stream):
+                B.dynts_decode_loop(cache.ctx, T, q, k, v, outs, cache.keep_idx, cache.new_len, evict_steps=flags,
+                                    out_step_stride=outs[0].numel())
+                B.dynts_update_scores(cache.ctx, 0)
+        torch.cuda.synchronize()
+        assert int(cache.status.item()) == 0 and int(cache.seq_len[0, 0].item()) == wl.steady_len + 3
+        n = wl.steady_len + 3
+        results.append((outs.clone(), cache.S[0, :, :, :n].clone(), cache.K[0, :, :, :n].clone(),
+                        cache.pos[0, :, :, :n].clone()))
+        cache.close()
+    for other in results[1:]:
+        for a, b in zip(results[0], other):
+            assert torch.equal(a, b)
