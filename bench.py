@@ -425,7 +425,8 @@ def run_cpu_baseline(wl, budget_s=15.0):
     o.next_pos[:] = o.pos[:, :, n0 - 1].max(axis=1) + 1
     o.steps_done[:] = wl.budget + wl.window + E  # a multiple of E: the next trigger is E steps away
     threads = orc.max_threads()
-    steps = torch.arange(10 ** 5, 10 ** 5 + max(4 * E, 1024))
+    n_multi = max(4 * E, 1024)                      # at most this many steps on all threads ...
+    steps = torch.arange(10 ** 5, 10 ** 5 + n_multi + 32)   # ... and up to 32 more on one thread
     q = gen.q(0, steps).to(torch.float64).numpy()
     k, v = gen.kv(0, steps)
     k, v = k.to(torch.float64).numpy(), v.to(torch.float64).numpy()
@@ -434,7 +435,7 @@ def run_cpu_baseline(wl, budget_s=15.0):
         s = gen.external_scores(steps).unsqueeze(-1).expand(len(steps), wl.batch, wl.n_kv_heads)
         s = s.to(torch.float64).contiguous().numpy()
     done, t0 = 0, time.perf_counter()
-    while done < len(steps):
+    while done < n_multi:
         o.step(q[done], k[done], v[done], s[done] if s is not None else None)
         done += 1
         if time.perf_counter() - t0 > budget_s and done >= 2:
