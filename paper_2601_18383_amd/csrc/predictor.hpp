@@ -50,7 +50,8 @@ __device__ __forceinline__ uint16_t f32_to_bf16(float x) {
 __device__ __forceinline__ float bf16_to_f32(uint16_t v) { return __uint_as_float((uint32_t)v << 16); }
 
 // k-steps (32 elements of K) one workgroup covers: its whole slice of the activations sits in 64 KB of LDS
-constexpr int mlp_slice_steps(int bt, int parts) { return 64 / (parts * bt); }
+// (128 KB for batches above 32, where the partial sums would otherwise outweigh the weights)
+constexpr int mlp_slice_steps(int bt, int parts) { return (bt >= 4 ? 128 : 64) / (parts * bt); }
 
 // BT = batch tiles of 16 (batch padded to 16 BT), PARTS = 1 (bf16 input) or 2 (hi + lo).
 // grid (ceil(m / 128), ceil(K / 32 / S)), 512 threads, S = mlp_slice_steps(BT, PARTS).
