@@ -104,6 +104,48 @@ def test_create_and_calls_before_bind(B):
     B.dynts_destroy(ctx)
 
 
+def test_argument_checks_of_the_wider_entry_points(B):
+    """Block scoring, predictor, paged binding, read-stream probe: every refusal comes before any launch."""
+    cfg = _cfg(B)
+    one = C.c_void_p(256)
+    need = B.dynts_workspace_bytes(cfg)
+    ctx = B.dynts_create(cfg)
+    assert B.lib.dynts_bind(ctx, *([one] * 7), one, need, one) == B.DYNTS_OK
+    # block scoring
+    assert B.dynts_score_block_scratch_bytes(cfg, 0) == 0 and B.dynts_score_block_scratch_bytes(cfg, 16) > 0
+    sb = B.dynts_score_block_scratch_bytes(cfg, 16)
+    assert B.lib.dynts_score_block(ctx, 0, None, None, 16, None, None, 1, one, sb, None) == B.DYNTS_ENULL
+    assert B.lib.dynts_score_block(ctx, 0, one, None, 0, None, None, 1, one, sb, None) == B.DYNTS_EINVAL
+    assert B.lib.dynts_score_block(ctx, 0, one, None, 16, None, None, 1, one, sb - 1, None) == B.DYNTS_EWORKSPACE
+    assert B.lib.dynts_score_block(ctx, 0, C.c_void_p(8), None, 16, None, None, 1, one, sb, None) == B.DYNTS_EINVAL
+    # paged binding: table too short for the capacity, missing stack; paged contexts refuse block scoring
+    args = [one, one, 64, one, 1, one, one, one, one, one, one, one, one, need, one]
+    assert B.lib.dynts_bind_paged(ctx, *args) == B.DYNTS_ECAPACITY            # 1 page of 64 slots < capacity
+    args[4] = (cfg.capacity + 63) // 64
+    assert B.lib.dynts_bind_paged(ctx, *(args[:5] + [None] + args[6:])) == B.DYNTS_ENULL
+    assert B.lib.dynts_bind_paged(ctx, *(args[:2] + [0] + args[3:])) == B.DYNTS_EINVAL
+    assert B.lib.dynts_bind_paged(ctx, *args) == B.DYNTS_OK
+    assert B.lib.dynts_score_block(ctx, 0, one, None, 16, None, None, 1, one, sb, None) == B.DYNTS_ESHAPE
+    B.dynts_destroy(ctx)
+    # predictor
+    w = B.dynts_predictor(64, 128, 32, 1, 0, 256, 0, 256, 0, 256, 0)
+    assert B.dynts_predict_scratch_bytes(w, 8) > 0 and B.dynts_predict_scratch_bytes(w, 0) == 0
+    nb = B.dynts_predict_scratch_bytes(w, 8)
+    assert B.lib.dynts_predict_scores(C.byref(w), None, 8, one, 1, one, nb, None, None, None) == B.DYNTS_ENULL
+    assert B.lib.dynts_predict_scores(C.byref(w), one, 8, one, 0, one, nb, None, None, None) == B.DYNTS_EINVAL
+    assert B.lib.dynts_predict_scores(C.byref(w), one, 8, one, 1, one, nb - 1, None, None, None) == B.DYNTS_EWORKSPACE
+    assert B.lib.dynts_predict_scores(C.byref(w), one, 8, one, 1, one, nb, one, None, None) == B.DYNTS_EINVAL
+    bad = B.dynts_predictor(64, 128, 40, 1, 0, 256, 0, 256, 0, 256, 0)        # m2 not a multiple of 16
+    assert B.lib.dynts_predict_scores(C.byref(bad), one, 8, one, 1, one, nb, None, None, None) == B.DYNTS_ESHAPE
+    assert B.lib.dynts_predictor_pack(None, 16, 32, one, None) == B.DYNTS_ENULL
+    assert B.lib.dynts_predictor_pack(one, 10, 32, C.c_void_p(512), None) == B.DYNTS_ESHAPE
+    assert B.lib.dynts_predictor_pack(one, 16, 32, one, None) == B.DYNTS_EINVAL   # in place is refused
+    # read-stream probe
+    assert B.lib.dynts_probe_read_stream(None, 1024, 4, 0, one, None, None, None) == B.DYNTS_ENULL
+    assert B.lib.dynts_probe_read_stream(one, 1000, 4, 0, one, None, None, None) == B.DYNTS_EINVAL
+    assert B.lib.dynts_probe_read_stream(one, 1024, 0, 0, one, None, None, None) == B.DYNTS_EINVAL
+
+
 def test_missing_library_is_an_import_error(monkeypatch, tmp_path):
     import importlib
     import paper_2601_18383_amd.binding as binding
