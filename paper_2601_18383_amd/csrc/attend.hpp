@@ -180,13 +180,13 @@ __global__ __launch_bounds__(W * 64, 2) void attend_kernel(const AttendParams p)
   const int G = p.G;
 
   const size_t unit = (size_t)b * p.Hkv + h;
-  // dense: this unit's rows; paged: the pools (see paged_base below)
+  // dense: this unit's rows; paged: the pools
   uint16_t *Kb = PAGED ? p.K : p.K + unit * (size_t)p.cap * D;
   uint16_t *Vb = PAGED ? p.V : p.V + unit * (size_t)p.cap * D;
   const int32_t *tb = PAGED ? p.block_table + unit * (size_t)p.max_pages : nullptr;
   // Paged addressing of one tile: the tile start is first pulled back into the tile that holds row end-1
-  // (so every clamped row stays in ONE page), then `delta` is the element offset that turns "row r of the
-  // unit" into "row r of that page" for all rows of the tile: address = pool + delta + r * D.
+  // (so every clamped row stays in ONE page); the tile is then loaded relative to that page: base = pool +
+  // page * 64 rows, rows and the clamp counted from the page's first slot.
   auto page_of = [&](int tp) -> int {
     int pi = tp / kPageSlots;
     pi = pi < p.max_pages ? pi : p.max_pages - 1;
@@ -197,9 +197,7 @@ __global__ __launch_bounds__(W * 64, 2) void attend_kernel(const AttendParams p)
     const int last_tile = (end - 1) & ~(kTile - 1);
     return tt < last_tile ? tt : last_tile;
   };
-  auto page_delta = [&](int tp, int pg) -> ptrdiff_t {
-    return ((ptrdiff_t)pg * kPageSlots - (ptrdiff_t)(tp & ~(kPageSlots - 1))) * D;
-  };
+  auto page_base = [&](int pg) -> size_t { return (size_t)pg * kPageSlots * D; };  // element offset of a page
   float *Sb = p.S + unit * (size_t)p.cap;
   unsigned char *vst = smem + wave * (kTile * VSTRIDE);
   const int vrow_l = lane / PIECES, vpiece = lane % PIECES;
@@ -235,9 +233,10 @@ __global__ __launch_bounds__(W * 64, 2) void attend_kernel(const AttendParams p)
     // The first tile's page is looked up right away and its 32 rows fetched whole (a tile lies inside one
     // page, and a page id is clamped into the pool, so the addresses are valid whatever the length turns
     // out to be; rows past the sequence hold finite stale data and meet masked logits and zero weights).
-    const ptrdiff_t d0 = page_delta(t, page_of(t));
-    load_k_tile<D>(kf, Kb + d0, t, r16, kg, t + kTile);
-    if (ATTEND) load_v_tile<D>(vf, Vb + d0, t, lane, t + kTile);
+    const size_t b0 = page_base(page_of(t));
+    const int tr = t & (kPageSlots - 1);
+    load_k_tile<D>(kf, Kb + b0, tr, r16, kg, tr + kTile);
+    if (ATTEND) load_v_tile<D>(vf, Vb + b0, tr, lane, tr + kTile);
   }
   __builtin_amdgcn_sched_barrier(0);
 
@@ -463,14 +462,18 @@ __global__ __launch_bounds__(W * 64, 2) void attend_kernel(const AttendParams p)
       }
     }
     const float s_cur = s_old;
-    ptrdiff_t dn = 0;   // paged: element offset of the next tile's page, and its clamped start
-    int tnp = tn;
+    // where the next tile is fetched from: (base, first row, row clamp), page-relative in the paged layout
+    size_t nb = 0;
+    int nt = tn, nk_end = k_last, nv_end = v_last;
     if (PAGED) {
-      tnp = clamp_tile(tn, k_last);
-      dn = page_delta(tnp, pg_nxt);
+      const int tnp = clamp_tile(tn, k_last), page_start = tnp & ~(kPageSlots - 1);
+      nb = page_base(pg_nxt);
+      nt = tnp - page_start;
+      nk_end = k_last - page_start;
+      nv_end = v_last - page_start;
       pg_nxt = page_of(clamp_tile(tn + kTile, k_last));
     }
-    load_k_tile<D>(kf, Kb + dn, tnp, r16, kg, k_last);
+    load_k_tile<D>(kf, Kb + nb, nt, r16, kg, nk_end);
     if (PENDING) {
       const int tok = tn + (lane & (kTile - 1));
       s_old = Sb[tok < p.cap ? tok : p.cap - 1];
@@ -540,7 +543,7 @@ __global__ __launch_bounds__(W * 64, 2) void attend_kernel(const AttendParams p)
       for (int it = 0; it < VIT; ++it)
         *reinterpret_cast<u32x4 *>(vst + (VROWS * it + vrow_l) * VSTRIDE + 16 * vpiece) = vf[it];
       wave_lds_fence();
-      load_v_tile<D>(vf, Vb + dn, tnp, lane, v_last);
+      load_v_tile<D>(vf, Vb + nb, nt, lane, nv_end);
 #pragma unroll
       for (int cb = 0; cb < CB; ++cb) {
         // V^T operand: lane (c = 16 cb + r16, kg) gets V[t + 16 s + 4 kg + i][c] as element 4 s + i.
