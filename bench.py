@@ -119,6 +119,7 @@ def read_stream_rates(B, nbytes, dev):
     (what a cache re-read every step can get from the memory-side cache) and a rotation of buffers that
     together exceed it (what HBM alone delivers).  Median of 20 launches each, best of three grid sizes."""
     import torch
+    nbytes = max(nbytes, 1 << 20)
     n_rot = max(2, (2 << 30) // nbytes)
     bufs = [torch.ones(nbytes // 4, dtype=torch.int32, device=dev) for _ in range(n_rot)]
     sink = torch.zeros(4, dtype=torch.int32, device=dev)
