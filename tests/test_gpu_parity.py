@@ -321,3 +321,61 @@ def test_long_cache_single_unit(B):
     assert n2 == M + 1000 + 10 and int(cache.seq_len.item()) == n2
     assert np.array_equal(f64(cache.K[0])[:, :, :n2], o.K[:, :, :n2]) and np.array_equal(f64(cache.V[0])[:, :, :n2], o.V[:, :, :n2])
     assert np.array_equal(i32(cache.pos[0])[:, :, :n2], o.pos[:, :, :n2])
+
+
+@pytest.mark.parametrize("external", [False, True])
+def test_native_loop_equals_single_calls(B, external):
+    """dynts_decode_loop over several layers (per-step input slabs, ragged activity, trigger steps, one output slab
+    per step) does exactly what the same calls issued one by one do: bit-identical caches and outputs."""
+    rng = np.random.default_rng(21)
+    dev = torch.device("cuda:0")
+    L, Nb, Hq, Hkv, d = 3, 4, 8, 2, 64
+    M, budget, window, E, T = 6, 20, 5, 9, 70
+    cap = M + budget + window + E
+    q = _bf16(rng, T, L, Nb, Hq, d).to(dev)
+    k = _bf16(rng, T, L, Nb, Hkv, d).to(dev)
+    v = _bf16(rng, T, L, Nb, Hkv, d).to(dev)
+    s = torch.from_numpy(rng.integers(0, 6, (T, Nb, Hkv)).astype(np.float32)).to(dev) if external else None
+    active = (rng.random((T, Nb)) < 0.85).astype(np.uint8)
+    active[:, 0] = 1
+    act = torch.from_numpy(active).to(dev)
+    # trigger steps from the schedule of the always-active sequence
+    flags = torch.zeros(T, dtype=torch.uint8)
+    for t in range(1, T + 1):
+        if t >= budget + window + E and (t - (budget + window + E)) % E == 0:
+            flags[t - 1] = 1
+    trig = torch.ones((T, Nb), dtype=torch.uint8, device=dev)   # every sequence is trimmed on a trigger step
+    K0, V0 = _bf16(rng, Nb, Hkv, M, d).to(dev), _bf16(rng, Nb, Hkv, M, d).to(dev)
+    m = torch.tensor([6, 2, 0, 4], dtype=torch.int32, device=dev)
+
+    def fresh():
+        c = B.Cache(L, Nb, Hq, Hkv, d, cap, budget, window, E, external_scores=external)
+        for l in range(L):
+            B.dynts_prefill(c.ctx, l, K0, V0, m)
+        return c
+
+    a, b_ = fresh(), fresh()
+    outs_a = torch.zeros((T, L, Nb, Hq, d), dtype=torch.float32, device=dev)
+    outs_b = torch.zeros_like(outs_a)
+    B.dynts_decode_loop(a.ctx, T, q, k, v, outs_a, a.keep_idx, a.new_len, s_new=s, active=act, evict_steps=flags,
+                        trigger=trig, out_step_stride=outs_a[0].numel())
+    for t in range(T):
+        for l in range(L):
+            B.dynts_decode_step(b_.ctx, l, q[t, l], k[t, l], v[t, l], outs_b[t, l], s_new=s[t] if external else None,
+                                active=act[t])
+            if flags[t]:
+                B.dynts_select_evict(b_.ctx, l, b_.keep_idx, b_.new_len, budget, trig[t])
+                B.dynts_compact(b_.ctx, l, b_.keep_idx, b_.new_len, trig[t])
+    for l in range(L):
+        B.dynts_update_scores(a.ctx, l)
+        B.dynts_update_scores(b_.ctx, l)
+    torch.cuda.synchronize()
+    assert torch.equal(outs_a, outs_b)
+    assert torch.equal(a.seq_len, b_.seq_len) and torch.equal(a.next_pos, b_.next_pos)
+    for l in range(L):
+        for bb in range(Nb):
+            n = int(a.seq_len[l, bb])
+            assert torch.equal(a.K[l, bb, :, :n], b_.K[l, bb, :, :n]) and torch.equal(a.V[l, bb, :, :n], b_.V[l, bb, :, :n])
+            assert torch.equal(a.S[l, bb, :, :n], b_.S[l, bb, :, :n]) and torch.equal(a.pos[l, bb, :, :n], b_.pos[l, bb, :, :n])
+    assert int(a.seq_len[0, 0]) < cap and int(flags.sum()) >= 3
+    assert int(a.status.item()) == 0 and int(b_.status.item()) == 0
