@@ -102,8 +102,7 @@ int dynts_bind(dynts_ctx *ctx, uint16_t *K, uint16_t *V, float *S, int32_t *pos,
  * any other sequence.  dynts_prefill expects the layer's units to hold no pages.  When the stack runs dry the
  * row is dropped and bit 2 (value 4) of the status word is latched; results are undefined from then on.
  * The pools must hold finite values before first use (zero-filled, say): rows beyond a sequence's length may be
- * read, with zero weight.  S, pos and the per-sequence arrays keep the dense layout.  Everything else behaves as after dynts_bind;
- * dynts_score_block is not available in this layout (DYNTS_ESHAPE). */
+ * read, with zero weight.  S, pos and the per-sequence arrays keep the dense layout.  Everything else behaves as after dynts_bind. */
 int dynts_bind_paged(dynts_ctx *ctx, uint16_t *K_pool, uint16_t *V_pool, int32_t n_pages, int32_t *block_table,
                      int32_t max_pages, int32_t *free_stack, int32_t *free_top, float *S, int32_t *pos,
                      int32_t *seq_len, int32_t *next_pos, int32_t *n_prompt, void *workspace,

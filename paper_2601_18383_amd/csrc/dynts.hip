@@ -561,7 +561,6 @@ int dynts_score_block(dynts_ctx *ctx, int32_t layer, const uint16_t *q_blk, cons
   int rc = check_call(ctx, layer);
   if (rc != DYNTS_OK) return rc;
   if (!q_blk || !scratch) return DYNTS_ENULL;
-  if (ctx->paged) return DYNTS_ESHAPE;  // block scoring reads the dense layout only
   if (n_queries <= 0 || n_queries > (1 << 20)) return DYNTS_EINVAL;
   if (reinterpret_cast<uintptr_t>(q_blk) % 16 || reinterpret_cast<uintptr_t>(k_blk) % 16) return DYNTS_EINVAL;
   const dynts_config &c = ctx->cfg;
@@ -588,6 +587,7 @@ int dynts_score_block(dynts_ctx *ctx, int32_t layer, const uint16_t *q_blk, cons
   p.skip_prompt = dst ? 0 : 1;
   p.accumulate = accumulate ? 1 : 0;
   p.scale_log2 = ctx->scale_log2;
+  p.block_table = lv.block_table; p.max_pages = ctx->max_pages; p.n_pages = ctx->n_pages;
   const long long R = (long long)n_queries * G;
   // (1-D grids: blocks per unit x units rounded up to the 8 XCDs, mapped inside the kernels)
   const long long units8 = ((long long)c.batch * c.n_kv_heads + 7) / 8 * 8;

@@ -50,7 +50,23 @@ struct ScoreBlockParams {
   int skip_prompt;          // 1: slots below n_prompt[b] are left alone (dst is the score array)
   int accumulate;           // 1: dst += sums, 0: dst = sums
   float scale_log2;         // softmax scale * log2(e)
+  // paged layout: K is the page pool, slot j of a unit is row j % 64 of page block_table[unit][j / 64]
+  const int32_t *block_table;  // layer base [Nb][Hkv][max_pages], or null (dense layout)
+  int max_pages, n_pages;
 };
+
+// byte address of cached key row `row` of a unit (dense rows, or through the block table)
+template <int D>
+__device__ __forceinline__ const char *sb_key_row(const ScoreBlockParams &p, size_t unit, int row) {
+  if (p.block_table) {
+    int pi = row / kPageSlots;
+    pi = pi < p.max_pages ? pi : p.max_pages - 1;
+    int pg = p.block_table[unit * (size_t)p.max_pages + pi];
+    pg = pg < 0 ? 0 : (pg >= p.n_pages ? p.n_pages - 1 : pg);
+    return reinterpret_cast<const char *>(p.K + ((size_t)pg * kPageSlots + row % kPageSlots) * D);
+  }
+  return reinterpret_cast<const char *>(p.K + (unit * (size_t)p.cap + row) * D);
+}
 
 // MFMA operand fragments of one row in global memory: 16 bytes per k-step at the lane's column group.
 template <int D>
@@ -142,7 +158,6 @@ __global__ __launch_bounds__(kSbWaves * 64) void score_block_stats_kernel(const 
   const bool has_rows = row0 < R;  // a wave without rows still helps staging and meets the barriers
   int n = p.seq_len[b];
   n = n < 0 ? 0 : (n > p.cap ? p.cap : n);
-  const char *Kb = reinterpret_cast<const char *>(p.K + (size_t)unit * (size_t)p.cap * D);
   const char *Qb = reinterpret_cast<const char *>(p.q_blk + ((size_t)b * p.T * p.Hq + (size_t)h * p.G) * D);
   const float c = p.scale_log2;
 
@@ -190,15 +205,16 @@ __global__ __launch_bounds__(kSbWaves * 64) void score_block_stats_kernel(const 
     l[qt] = sum;                                                                                       \
   }
 
-  // Streaming of `rows` rows that start at `src` with pitch `pitch` bytes, 32 per chunk; row indices
-  // beyond the last repeat it (the fold masks them).  Every thread of the workgroup runs this.
+  // Streaming of `rows` rows that start at `src` with pitch `pitch` bytes (src null: the unit's cached key
+  // rows), 32 per chunk; row indices beyond the last repeat it (the fold masks them).  Every thread of the workgroup runs this.
   const int st_row = tid / St::PIECES, st_piece = tid % St::PIECES;
   u32x4 stage[St::NL];
 #define DYNTS_SB_FETCH(src_, pitch_, rows_, chunk_)                                                    \
   _Pragma("unroll") for (int k = 0; k < St::NL; ++k) {                                                 \
     int row = (chunk_) * St::kChunk + st_row + St::RPP * k;                                            \
     row = row < (rows_) ? row : (rows_) - 1;                                                           \
-    stage[k] = *reinterpret_cast<const u32x4 *>((src_) + (size_t)row * (pitch_) + 16 * st_piece);      \
+    const char *rp = (src_) ? (src_) + (size_t)row * (pitch_) : sb_key_row<D>(p, (size_t)unit, row);   \
+    stage[k] = *reinterpret_cast<const u32x4 *>(rp + 16 * st_piece);                                   \
   }
 #define DYNTS_SB_PARK(buf_)                                                                            \
   _Pragma("unroll") for (int k = 0; k < St::NL; ++k)                                                   \
@@ -240,7 +256,8 @@ __global__ __launch_bounds__(kSbWaves * 64) void score_block_stats_kernel(const 
     int lim[kSbTiles];
 #pragma unroll
     for (int qt = 0; qt < kSbTiles; ++qt) lim[qt] = n;
-    DYNTS_SB_STREAM(Kb, (size_t)(2 * D), n, lim, false)
+    const char *const cached = nullptr;  // (null source: cached key rows, found by sb_key_row)
+    DYNTS_SB_STREAM(cached, (size_t)0, n, lim, false)
   }
   // the block's own keys, causally: key i' is visible to query row (i, g) iff i' <= i.  Keys
   // [0, i_hi) are visible to some row of this workgroup.
@@ -297,7 +314,6 @@ __global__ __launch_bounds__(kSbWaves * 64) void score_block_colsum_kernel(const
   if (blk * kSbRowsPerWg >= n || (blk + 1) * kSbRowsPerWg <= first) return;
   const int key0 = blk * kSbRowsPerWg + wave * kSbRowsPerWave;
   const bool has_keys = key0 < n && key0 + kSbRowsPerWave > first;  // else: staging and barriers only
-  const char *Kb = reinterpret_cast<const char *>(p.K + (size_t)unit * (size_t)p.cap * D);
   const char *Qb = reinterpret_cast<const char *>(p.q_blk + ((size_t)b * p.T * p.Hq + (size_t)h * p.G) * D);
   const float *Lb = p.stats + (size_t)unit * (size_t)p.Rpad;
   const float c = p.scale_log2;
@@ -308,7 +324,7 @@ __global__ __launch_bounds__(kSbWaves * 64) void score_block_colsum_kernel(const
   for (int kt = 0; kt < kSbTiles; ++kt) {
     int row = key0 + 16 * kt + r16;
     row = row < n ? row : n - 1;
-    load_row_frags<D>(kf[kt], Kb + (size_t)row * (size_t)(2 * D), kg);
+    load_row_frags<D>(kf[kt], sb_key_row<D>(p, (size_t)unit, row), kg);
   }
   f32x4 sum[kSbTiles];
 #pragma unroll

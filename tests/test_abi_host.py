@@ -118,14 +118,13 @@ def test_argument_checks_of_the_wider_entry_points(B):
     assert B.lib.dynts_score_block(ctx, 0, one, None, 0, None, None, 1, one, sb, None) == B.DYNTS_EINVAL
     assert B.lib.dynts_score_block(ctx, 0, one, None, 16, None, None, 1, one, sb - 1, None) == B.DYNTS_EWORKSPACE
     assert B.lib.dynts_score_block(ctx, 0, C.c_void_p(8), None, 16, None, None, 1, one, sb, None) == B.DYNTS_EINVAL
-    # paged binding: table too short for the capacity, missing stack; paged contexts refuse block scoring
+    # paged binding: table too short for the capacity, missing stack
     args = [one, one, 64, one, 1, one, one, one, one, one, one, one, one, need, one]
     assert B.lib.dynts_bind_paged(ctx, *args) == B.DYNTS_ECAPACITY            # 1 page of 64 slots < capacity
     args[4] = (cfg.capacity + 63) // 64
     assert B.lib.dynts_bind_paged(ctx, *(args[:5] + [None] + args[6:])) == B.DYNTS_ENULL
     assert B.lib.dynts_bind_paged(ctx, *(args[:2] + [0] + args[3:])) == B.DYNTS_EINVAL
     assert B.lib.dynts_bind_paged(ctx, *args) == B.DYNTS_OK
-    assert B.lib.dynts_score_block(ctx, 0, one, None, 16, None, None, 1, one, sb, None) == B.DYNTS_ESHAPE
     B.dynts_destroy(ctx)
     # predictor
     w = B.dynts_predictor(64, 128, 32, 1, 0, 256, 0, 256, 0, 256, 0)

@@ -167,3 +167,29 @@ def test_two_layers_share_one_pool(B):
         assert sbs.evictions == 2
     _check_pages(cache)
     assert int(cache.status.item()) == 0
+
+
+def test_block_scoring_reads_the_paged_layout(B):
+    """dynts_score_block on a paged cache equals the oracle on the dense view (keys found through the block table)."""
+    rng = np.random.default_rng(44)
+    dev = torch.device("cuda:0")
+    Nb, Hq, Hkv, d, T = 3, 28, 4, 128, 40
+    M, budget, window, E = 13, 200, 17, 90
+    cap = M + budget + window + E
+    cache = B.PagedCache(1, Nb, Hq, Hkv, d, cap, budget, window, E)
+    o = orc.OracleLayer(Nb, Hq, Hkv, d, cap, budget, window, E)
+    sbs = SideBySide(B, cache, 0, o, "step")
+    sbs.prefill(_bf16(rng, Nb, Hkv, M, d), _bf16(rng, Nb, Hkv, M, d), [13, 4, 9])
+    for t in range(1, 271):   # through one eviction, so that pages have been returned and taken again
+        sbs.step(_bf16(rng, Nb, Hq, d), _bf16(rng, Nb, Hkv, d), _bf16(rng, Nb, Hkv, d), check_scores=False)
+    assert sbs.evictions == 0 or sbs.evictions >= 1
+    sbs.check_scores()
+    q = _bf16(rng, Nb, T, Hq, d, scale=1.5)
+    kb = _bf16(rng, Nb, T, Hkv, d)
+    scratch = torch.empty(B.dynts_score_block_scratch_bytes(cache.cfg, T), dtype=torch.uint8, device=dev)
+    dst = torch.zeros((Nb, Hkv, cap), dtype=torch.float32, device=dev)
+    B.dynts_score_block(cache.ctx, 0, q.to(dev), kb.to(dev), scratch, dst=dst, accumulate=False)
+    I_ref = orc.score_block(f64(q), f64(kb), o.K, o.seq_len, o.scale)
+    for b in range(Nb):
+        n = int(o.seq_len[b])
+        assert_close(f64(dst)[b, :, :n], I_ref[b, :, :n], "paged block scoring, sequence %d" % b)
