@@ -62,7 +62,7 @@ typedef struct dynts_config {
   int32_t n_q_heads;
   int32_t n_kv_heads;
   int32_t head_dim;
-  int32_t capacity;     /* cap: slots per (sequence, KV head); >= prompt + budget + window + evict_every */
+  int32_t capacity;     /* cap: slots per (sequence, KV head); >= prompt + budget + window + evict_every, <= 2^22 */
   int32_t budget;       /* selection-window slots kept by a trigger (the k of top-k, default k_keep) */
   int32_t window;       /* local-window slots, always kept */
   int32_t evict_every;  /* trigger period in steps = eviction volume K of Sec. 5 */

@@ -43,6 +43,7 @@ int check_config(const dynts_config *c) {
   if (c->n_q_heads / c->n_kv_heads > 16) return DYNTS_ESHAPE;
   if (c->n_kv_heads * (c->head_dim / 8) > 1024) return DYNTS_ESHAPE;
   if (c->batch > 65535 || c->n_kv_heads > 65535) return DYNTS_ESHAPE;
+  if (c->capacity > (1 << 22)) return DYNTS_ESHAPE;  // row offsets inside a unit are 32-bit byte offsets
   if ((long long)c->capacity < (long long)c->budget + c->window + c->evict_every) return DYNTS_ECAPACITY;
   return DYNTS_OK;
 }

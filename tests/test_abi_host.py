@@ -53,6 +53,7 @@ def _cfg(B, **kw):
     (dict(score_mode=2), -1), (dict(softmax_scale=-1.0), -1), (dict(softmax_scale=float("nan")), -1),
     (dict(head_dim=96), -3), (dict(n_q_heads=7), -3), (dict(n_q_heads=34, n_kv_heads=2), -3),
     (dict(capacity=335), -4), (dict(n_kv_heads=128, n_q_heads=128, head_dim=128), -3),
+    (dict(capacity=(1 << 22) + 1), -3),
 ])
 def test_create_rejects_bad_config(B, kw, code):
     cfg = _cfg(B, **kw)
