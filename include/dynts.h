@@ -141,7 +141,8 @@ int dynts_update_scores(dynts_ctx *ctx, int32_t layer, void *stream);
 int dynts_decode_attend_update(dynts_ctx *ctx, int32_t layer, const uint16_t *q,
                                const uint8_t *active, float *out, float *lse, void *stream);
 
-/* One whole decode step of a layer in one pass: dynts_append + dynts_decode_attend_update. */
+/* One whole decode step of a layer in one pass: dynts_append + dynts_decode_attend_update.  A sequence whose
+ * cache is already full is left alone in this step (nothing appended, attended or scored; status bit 0). */
 int dynts_decode_step(dynts_ctx *ctx, int32_t layer, const uint16_t *q, const uint16_t *k_new,
                       const uint16_t *v_new, const float *s_new, const uint8_t *active,
                       float *out, float *lse, void *stream);
