@@ -36,7 +36,7 @@ def _run(B, rng, d, m1, m2, batch, act, bias=True, n_rep=1, pack=True):
     ref = orc.predictor(f64(h), *[f64(w) if w is not None else None for w in ws], act)
     got = f64(s)
     for r in range(n_rep):
-        worst = assert_close(got[:, r], ref, "predictor d=%d batch=%d act=%d" % (d, batch, act))
+        worst = assert_close(got[:, r], ref, "predictor d=%d batch=%d act=%d" % (d, batch, act), tight=1e-4)
     assert np.all(got == got[:, :1])
     return worst
 
@@ -113,7 +113,7 @@ def test_paper_inference_mode_end_to_end(B):
         h = bf(Nb, d_model)
         B.dynts_predict_scores(pred, h.to(dev), s_dev)
         s_ref = orc.predictor(f64(h), *[f64(w) for w in ws], orc.ACT_SILU)
-        assert_close(f64(s_dev)[:, 0], s_ref, "predicted score, step %d" % t)
+        assert_close(f64(s_dev)[:, 0], s_ref, "predicted score, step %d" % t, tight=1e-4)
         # both sides append the HIP path's fp32 score, so that the selection below is decided on identical
         # numbers (the predictor's own parity is asserted just above)
         sbs.step(bf(Nb, Hq, d_head), bf(Nb, Hkv, d_head), bf(Nb, Hkv, d_head), s=s_dev.cpu(), check_scores=(t % 9 == 0))
