@@ -133,16 +133,24 @@ __device__ __forceinline__ void load_v_tile(u32x4 (&vf)[kTile / (64 / (D / 8))],
 }
 // Cross-workgroup traffic inside one launch (split partials, arrival counters) goes through
 // device-coherent accesses: relaxed agent-scope atomics compile to sc1 loads/stores that are
-// written through to, and read from, the level all XCDs share.  A store counts as complete
-// (vmcnt) only once it is visible there, so "wait for my stores, then bump the counter"
-// orders them without a cache-wide write-back/invalidate fence.
+// written through to, and read from, the level all XCDs share.  The hand-off of a partial is:
+//   every wave that stored a piece waits until its own vector-memory operations have completed
+//   (wait_own_stores: s_waitcnt vmcnt(0); a write-through store is only counted as complete once
+//   it has been acknowledged by the shared level), THEN the workgroup barrier, THEN one thread's
+//   arrival atomic at that same level.  A workgroup that reads the arrival count as complete
+//   issues its (sc1) merge loads after the atomic has returned, so they reach the shared level
+//   after every store they depend on has been acknowledged there.  No cache-wide write-back or
+//   invalidate is needed because no ordinary cached access ever touches these words in a launch.
 __device__ __forceinline__ void coherent_store(float *p, float v) {
   __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
 __device__ __forceinline__ float coherent_load(const float *p) {
   return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
-__device__ __forceinline__ void wait_own_stores() { __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup"); }
+// The wave's outstanding vector-memory operations (stores included) have all completed when this
+// returns.  Spelt as the instruction itself: a workgroup-scope release fence emits no vector-memory
+// wait on this target, and an agent-scope one adds a write-back of the whole L2.
+__device__ __forceinline__ void wait_own_stores() { asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); }
 
 // 2^x by the hardware instruction alone (v_exp_f32, ~1 ulp).  Arguments here are <= 0 up to
 // rounding; results below 2^-126 flush to zero, which is far under what the sums resolve.
@@ -170,6 +178,7 @@ __global__ __launch_bounds__(W * 64, 2) void attend_kernel(const AttendParams p)
   __shared__ float sm_l[kWaves][16];
   __shared__ float sm_fin[2][16];
   __shared__ uint32_t sm_flag;
+  __shared__ int32_t sm_hdr[5];
 
   DYNTS_STAMP(0);
   const int tid = threadIdx.x;
@@ -214,11 +223,19 @@ __global__ __launch_bounds__(W * 64, 2) void attend_kernel(const AttendParams p)
   // the first tile, whose addresses depend on kernel arguments only (rows clamped to the end
   // of the allocation; what lies past the sequence is masked once its length is known); then
   // the query and the statistics.
-  const int act_raw = p.active ? (int)p.active[b] : 1;
-  const int len_raw = p.seq_len[b];
-  const int prev_raw = PENDING ? p.nprev[b] : 0;
-  const int M = p.n_prompt[b];
-  const int pos_new_all = APPEND ? p.next_pos[b] : 0;
+  //
+  // The per-sequence words.  seq_len, nprev and next_pos are REWRITTEN during this launch, by the last
+  // workgroup of the sequence to check in, so only wave 0 reads them (the wave of the thread that checks
+  // in, which it does after these loads have returned); the other waves get them through LDS behind the
+  // barrier below.  Lanes 0..4 of wave 0 fetch one word each with a vector load, so nothing waits here
+  // (uniform addresses would become scalar loads that the wave must wait for before its tile loads).
+  int hdr_word = 1;  // lane 4 without a mask: active
+  if (tid < 4) {
+    const int32_t *src = tid == 0 ? p.seq_len : (tid == 1 ? p.nprev : (tid == 2 ? p.next_pos : p.n_prompt));
+    hdr_word = src[b];
+  } else if (tid == 4 && p.active) {
+    hdr_word = (int)p.active[b];
+  }
   __builtin_amdgcn_sched_barrier(0);
   bf16x8 kf[2][KS];
   u32x4 vf[VIT];
@@ -280,9 +297,20 @@ __global__ __launch_bounds__(W * 64, 2) void attend_kernel(const AttendParams p)
     for (int ks = 0; ks < KS; ++ks) kn[ks] = load_bf16x8(knew + 32 * ks + 8 * kg);  // every operand row is k_new
 #pragma unroll
     for (int cb = 0; cb < CB; ++cb) vn[cb] = *reinterpret_cast<const uint2 *>(vnew + 16 * cb + 4 * kg);
-    pos_new = pos_new_all;
     if (p.s_new) s_init = p.s_new[unit];
   }
+
+  // hand the three per-sequence words from wave 0 to the whole workgroup.  Everything above was only
+  // ISSUED (the tile loads are still in flight across this barrier); wave 0 waits for its three words,
+  // which it would have had to do next anyway.
+  if (tid < 5) sm_hdr[tid] = hdr_word;
+  __syncthreads();
+  const int len_raw = sm_hdr[0];
+  const int prev_raw = PENDING ? sm_hdr[1] : 0;
+  const int pos_new_all = APPEND ? sm_hdr[2] : 0;
+  const int M = sm_hdr[3];
+  const int act_raw = sm_hdr[4];
+  pos_new = pos_new_all;
 
   // ---- what this launch does for sequence b (identical in every workgroup of b) ---------
   // n_rows cache slots are attended from the cache; when a token is appended in the same
@@ -320,10 +348,12 @@ __global__ __launch_bounds__(W * 64, 2) void attend_kernel(const AttendParams p)
   for (int i = 0; i < 4; ++i)  // inv_l = 0 switches padded heads and idle sequences off
     inv_lprev[i] = (PENDING && 4 * kg + i < G && n_prev > 0) ? 1.0f / inv_lprev[i] : 0.f;
 
-  // Every workgroup of the sequence checks in as soon as its reads of seq_len / nprev / next_pos
-  // have come back (it works from registers afterwards); the last one to check in advances them.
-  // The check-in is issued early and its answer looked at later, so it costs no round trip at
-  // the end of the workgroup.
+  // Every workgroup of the sequence checks in once its reads of seq_len / nprev / next_pos have come
+  // back: thread 0 checks in, and its own wave made those reads and has already consumed their values
+  // (they went through LDS above), so the atomic is issued after they completed.  The last workgroup
+  // to check in advances the three words -- by then no workgroup of the sequence has a read of them
+  // outstanding.  The check-in is issued early and its answer looked at later, so it costs no round
+  // trip at the end of the workgroup.
   uint32_t seq_ticket = 0xffffffffu;
   auto seq_checkin = [&]() {
     if (ATTEND && tid == 0) seq_ticket = atomicAdd(&p.seq_cnt[b], 1u);
