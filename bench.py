@@ -149,7 +149,7 @@ def run_gpu(args, wl):
     props = torch.cuda.get_device_properties(0)
     log("device: %s, %d CUs, %.0f GiB" % (props.name, props.multi_processor_count, props.total_memory / 2 ** 30))
     gen = synth.Synth(wl, dev)
-    cache = (B.PagedCache if args.paged else B.Cache).for_workload(wl, device=dev)
+    cache = (B.PagedCache if args.paged else B.Cache).for_workload(wl, device=dev, launch_shape=args.launch_shape)
     L = wl.n_layers
     for l in range(L):
         K0, V0 = gen.prompt_kv(l)
@@ -510,10 +510,14 @@ def main():
     ap.add_argument("--full-kv", action="store_true",
                     help="the comparison run without eviction: same inputs, a cache that holds every token, "
                          "attention only (no score is kept)")
+    ap.add_argument("--launch-shape", default=None, metavar="WGS,WAVES",
+                    help="tuning: dynts_set_launch_shape(target workgroups, waves per workgroup) instead of the default")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run three plain 1 GiB device copies (a kernel of known traffic, for scaling "
                          "rocprofv3's FETCH_SIZE / WRITE_SIZE counters)")
     args = ap.parse_args()
+    if args.launch_shape:
+        args.launch_shape = tuple(int(x) for x in args.launch_shape.split(","))
     if args.gpus != 1:
         sys.exit("bench.py measures one MI355X: the decode path shards over sequences and KV heads "
                  "without communication, and this build runs on a single GPU only (--gpus 1).")

@@ -85,6 +85,16 @@ int dynts_destroy(dynts_ctx *ctx);
  * softmax statistics of the deferred score update).  0 if cfg is invalid. */
 size_t dynts_workspace_bytes(const dynts_config *cfg);
 
+/* Launch shape of the attention kernel, for tuning and for tests that must reach a particular shape at a
+ * small size: the cache of a (sequence, KV head) is split over about target_workgroups / (batch * n_kv_heads)
+ * workgroups (at least one; 0 = the default, one workgroup per compute unit) of waves_per_workgroup waves
+ * (4 or 8; 0 = the default, 8).  Results do not depend on the shape beyond rounding order.  Changes the
+ * workspace layout: call it before dynts_bind (it unbinds), and size the workspace with
+ * dynts_ctx_workspace_bytes. */
+int dynts_set_launch_shape(dynts_ctx *ctx, int32_t target_workgroups, int32_t waves_per_workgroup);
+/* Bytes of workspace this context needs (= dynts_workspace_bytes(cfg) unless the launch shape was changed). */
+size_t dynts_ctx_workspace_bytes(const dynts_ctx *ctx);
+
 /* Attach the caller's device buffers (layout above).  `workspace` must be 256-byte aligned
  * and zero-filled once by the caller before first use; `status` is one int32, zeroed by
  * the caller.  Binding resets the context's deferred-update bookkeeping. */
@@ -150,7 +160,8 @@ int dynts_decode_step(dynts_ctx *ctx, int32_t layer, const uint16_t *q, const ui
 /* KV-cache selection (Sec. 4.2, third paragraph): for every sequence with trigger[b] != 0
  * (uint8 [Nb], NULL = all) and every KV head keep all question slots, the last `window`
  * slots, and of the slots between them the k_keep with the highest score (ties: lower
- * position first).  keep_idx int32 [Nb][Hkv][keep_stride] receives the retained slots in
+ * position first -- decided by SLOT order: the kernel never reads `pos`, it relies on the
+ * invariant that slots are in position order, which appends and the stable compaction keep).  keep_idx int32 [Nb][Hkv][keep_stride] receives the retained slots in
  * ascending order, new_len int32 [Nb] their count (seq_len[b] where not triggered or when
  * the selection window holds <= k_keep slots).  k_keep < 0 means cfg.budget.  Applies an
  * outstanding score accumulation first.  NaN scores give an unspecified (in-bounds) choice. */
@@ -222,7 +233,8 @@ int dynts_score_block(dynts_ctx *ctx, int32_t layer, const uint16_t *q_blk, cons
  *   h bf16 [batch][d], batch <= 128;  d and m1 multiples of 32, m2 a multiple of 16.
  *   s_out fp32 [batch][n_rep]: the score of sequence b written n_rep times (n_rep = n_kv_heads gives the
  *     [Nb][Hkv] layout of s_new: one score per token for every head, as in the paper).
- *   scratch: >= dynts_predict_scratch_bytes bytes, 256-byte aligned, contents irrelevant.
+ *   scratch: >= dynts_predict_scratch_bytes bytes, 256-byte aligned, zero-filled once by the caller before its
+ *     first use (it may be shared by calls that are stream-ordered with respect to each other).
  *   start/stop: optional hipEvent_t handles attached to the first and the last kernel of the call. */
 #define DYNTS_ACT_NONE 0
 #define DYNTS_ACT_RELU 1

@@ -24,6 +24,7 @@ EXPORTS = [
     "dynts_decode_loop", "dynts_set_kernel_events", "dynts_set_kernel_event_list", "dynts_probe_read_stream",
     "dynts_score_block_scratch_bytes", "dynts_score_block",
     "dynts_predict_scratch_bytes", "dynts_predict_scores", "dynts_predictor_pack", "dynts_bind_paged",
+    "dynts_set_launch_shape", "dynts_ctx_workspace_bytes",
 ]
 
 
@@ -57,6 +58,9 @@ def _load():
     lib.dynts_destroy.argtypes = [vp]
     lib.dynts_workspace_bytes.restype = sz
     lib.dynts_workspace_bytes.argtypes = [C.POINTER(dynts_config)]
+    lib.dynts_set_launch_shape.argtypes = [vp, i32, i32]
+    lib.dynts_ctx_workspace_bytes.restype = sz
+    lib.dynts_ctx_workspace_bytes.argtypes = [vp]
     lib.dynts_bind.argtypes = [vp] * 9 + [sz, vp]
     lib.dynts_bind_paged.argtypes = [vp, vp, vp, i32, vp, i32, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
     lib.dynts_prefill.argtypes = [vp, i32, vp, vp, i32, vp, vp]
@@ -143,6 +147,14 @@ def dynts_destroy(ctx):
 
 def dynts_workspace_bytes(cfg):
     return int(lib.dynts_workspace_bytes(C.byref(cfg)))
+
+
+def dynts_set_launch_shape(ctx, target_workgroups=0, waves_per_workgroup=0):
+    _check(lib.dynts_set_launch_shape(ctx, target_workgroups, waves_per_workgroup), "dynts_set_launch_shape")
+
+
+def dynts_ctx_workspace_bytes(ctx):
+    return int(lib.dynts_ctx_workspace_bytes(ctx))
 
 
 def dynts_bind(ctx, K, V, S, pos, seq_len, next_pos, n_prompt, workspace, status):
@@ -262,7 +274,7 @@ class Predictor:
                                  _ptr(b1, torch.float32), _ptr(W2, torch.bfloat16), _ptr(b2, torch.float32),
                                  _ptr(w3, torch.bfloat16), _ptr(b3, torch.float32))
         need = max(dynts_predict_scratch_bytes(self.w, nb) for nb in (16, 32, 64, max_batch) if nb <= max_batch)
-        self.scratch = torch.empty(max(need, 256), dtype=torch.uint8, device=W1.device)
+        self.scratch = torch.zeros(max(need, 256), dtype=torch.uint8, device=W1.device)
 
 
 def dynts_predictor_pack(W, stream=None):
@@ -281,11 +293,13 @@ class PagedCache:
     `K` and `V` give a dense [L][Nb][Hkv][cap][d] copy gathered through the block table (for inspection)."""
 
     def __init__(self, n_layers, batch, n_q_heads, n_kv_heads, head_dim, capacity, budget, window, evict_every,
-                 n_pages=None, softmax_scale=0.0, external_scores=False, device="cuda:0"):
+                 n_pages=None, softmax_scale=0.0, external_scores=False, device="cuda:0", launch_shape=None):
         self.cfg = make_config(n_layers, batch, n_q_heads, n_kv_heads, head_dim, capacity, budget, window,
                                evict_every, softmax_scale,
                                DYNTS_SCORE_EXTERNAL if external_scores else DYNTS_SCORE_ACCUMULATE)
         self.ctx = dynts_create(self.cfg)
+        if launch_shape is not None:
+            dynts_set_launch_shape(self.ctx, *launch_shape)
         dev = torch.device(device)
         L, Nb, Hkv, cap, d = n_layers, batch, n_kv_heads, capacity, head_dim
         self.max_pages = (cap + PAGE_SLOTS - 1) // PAGE_SLOTS
@@ -301,17 +315,17 @@ class PagedCache:
         self.next_pos = torch.zeros((L, Nb), dtype=torch.int32, device=dev)
         self.n_prompt = torch.zeros((Nb,), dtype=torch.int32, device=dev)
         self.status = torch.zeros((1,), dtype=torch.int32, device=dev)
-        self.workspace = torch.zeros((dynts_workspace_bytes(self.cfg),), dtype=torch.uint8, device=dev)
+        self.workspace = torch.zeros((dynts_ctx_workspace_bytes(self.ctx),), dtype=torch.uint8, device=dev)
         self.keep_idx = torch.zeros((Nb, Hkv, cap), dtype=torch.int32, device=dev)
         self.new_len = torch.zeros((Nb,), dtype=torch.int32, device=dev)
         dynts_bind_paged(self.ctx, self.K_pool, self.V_pool, self.block_table, self.free_stack, self.free_top, self.S,
                          self.pos, self.seq_len, self.next_pos, self.n_prompt, self.workspace, self.status)
 
     @classmethod
-    def for_workload(cls, wl, device="cuda:0", n_layers=None, n_pages=None):
+    def for_workload(cls, wl, device="cuda:0", n_layers=None, n_pages=None, launch_shape=None):
         return cls(wl.n_layers if n_layers is None else n_layers, wl.batch, wl.n_q_heads, wl.n_kv_heads,
                    wl.head_dim, wl.capacity, wl.budget, wl.window, wl.evict_every, n_pages=n_pages,
-                   external_scores=wl.external_scores, device=device)
+                   external_scores=wl.external_scores, device=device, launch_shape=launch_shape)
 
     def _dense(self, pool):
         idx = self.block_table.clamp(min=0).long()                      # [L][Nb][Hkv][max_pages]
@@ -367,11 +381,14 @@ class Cache:
     """Device buffers of one context, allocated with torch and bound; marshalling only."""
 
     def __init__(self, n_layers, batch, n_q_heads, n_kv_heads, head_dim, capacity, budget, window,
-                 evict_every, softmax_scale=0.0, external_scores=False, device="cuda:0"):
+                 evict_every, softmax_scale=0.0, external_scores=False, device="cuda:0", launch_shape=None):
+        """launch_shape: None or (target_workgroups, waves_per_workgroup) for dynts_set_launch_shape."""
         self.cfg = make_config(n_layers, batch, n_q_heads, n_kv_heads, head_dim, capacity, budget, window,
                                evict_every, softmax_scale,
                                DYNTS_SCORE_EXTERNAL if external_scores else DYNTS_SCORE_ACCUMULATE)
         self.ctx = dynts_create(self.cfg)
+        if launch_shape is not None:
+            dynts_set_launch_shape(self.ctx, *launch_shape)
         dev = torch.device(device)
         L, Nb, Hkv, cap, d = n_layers, batch, n_kv_heads, capacity, head_dim
         self.K = torch.zeros((L, Nb, Hkv, cap, d), dtype=torch.bfloat16, device=dev)
@@ -382,17 +399,17 @@ class Cache:
         self.next_pos = torch.zeros((L, Nb), dtype=torch.int32, device=dev)
         self.n_prompt = torch.zeros((Nb,), dtype=torch.int32, device=dev)
         self.status = torch.zeros((1,), dtype=torch.int32, device=dev)
-        self.workspace = torch.zeros((dynts_workspace_bytes(self.cfg),), dtype=torch.uint8, device=dev)
+        self.workspace = torch.zeros((dynts_ctx_workspace_bytes(self.ctx),), dtype=torch.uint8, device=dev)
         self.keep_idx = torch.zeros((Nb, Hkv, cap), dtype=torch.int32, device=dev)
         self.new_len = torch.zeros((Nb,), dtype=torch.int32, device=dev)
         dynts_bind(self.ctx, self.K, self.V, self.S, self.pos, self.seq_len, self.next_pos, self.n_prompt,
                    self.workspace, self.status)
 
     @classmethod
-    def for_workload(cls, wl, device="cuda:0", n_layers=None):
+    def for_workload(cls, wl, device="cuda:0", n_layers=None, launch_shape=None):
         return cls(wl.n_layers if n_layers is None else n_layers, wl.batch, wl.n_q_heads, wl.n_kv_heads,
                    wl.head_dim, wl.capacity, wl.budget, wl.window, wl.evict_every,
-                   external_scores=wl.external_scores, device=device)
+                   external_scores=wl.external_scores, device=device, launch_shape=launch_shape)
 
     def close(self):
         if self.ctx is not None:

@@ -60,15 +60,15 @@ struct AttendParams {
   uint16_t *qnext;          // [Nb][Hq][D] where this call's query is kept for the next deferred update
   float *mlprev;            // [Nb][Hq][2] (max in log2 units, sum) of the deferred update
   int32_t *nprev;           // [Nb] slots the deferred update covers (0 = none)
-  float *part_o;            // [Nb][Hkv][nsplit][G][D]
-  float *part_ml;           // [Nb][Hkv][nsplit][G][2]
-  uint32_t *unit_cnt;       // [Nb][Hkv] arrival counters, zero between launches
+  uint64_t *part_o;         // [Nb][Hkv][nsplit][G][D]  (tag << 32 | fp32 bits)
+  uint64_t *part_ml;        // [Nb][Hkv][nsplit][G][2]
+  uint32_t tag;             // this launch's serial number (never 0)
+  uint32_t *unit_cnt;       // [Nb][Hkv] ticket counters, zero between launches
   uint32_t *seq_cnt;        // [Nb]      arrival counters, zero between launches
   int32_t *status;
   int Nb, Hq, Hkv, G, cap, nsplit;
   int track;                // 1: scores are accumulated from attention (save q and statistics)
   float scale_log2;         // softmax scale * log2(e)
-  unsigned long long *trace;  // timestamps per workgroup (builds with -DDYNTS_TRACE only), else null
   // paged layout only: K and V are page pools [n_pages][kPageSlots][D]; slot j of a unit lives in page
   // block_table[unit][j / kPageSlots], row j % kPageSlots
   const int32_t *block_table;  // layer base, [Nb][Hkv][max_pages]
@@ -80,15 +80,6 @@ struct AttendParams {
 
 constexpr int kPageSlots = 64;  // slots per page: two tiles, so a tile never straddles pages
 
-#ifdef DYNTS_TRACE
-#define DYNTS_STAMP(slot)                                                                         \
-  do {                                                                                           \
-    if (p.trace && threadIdx.x == 0)                                                             \
-      p.trace[(((size_t)blockIdx.z * gridDim.y + blockIdx.y) * gridDim.x + blockIdx.x) * 8 + (slot)] = wall_clock64(); \
-  } while (0)
-#else
-#define DYNTS_STAMP(slot) do {} while (0)
-#endif
 
 __device__ __forceinline__ u32x4 load_u32x4(const uint16_t *p) { return *reinterpret_cast<const u32x4 *>(p); }
 __device__ __forceinline__ void store_u32x4(uint16_t *p, u32x4 v) { *reinterpret_cast<u32x4 *>(p) = v; }
@@ -131,26 +122,34 @@ __device__ __forceinline__ void load_v_tile(u32x4 (&vf)[kTile / (64 / (D / 8))],
     vf[it] = *reinterpret_cast<const u32x4 *>(base + ((uint32_t)row * (uint32_t)(2 * D) + lane_off));
   }
 }
-// Cross-workgroup traffic inside one launch (split partials, arrival counters) goes through
-// device-coherent accesses: relaxed agent-scope atomics compile to sc1 loads/stores that are
-// written through to, and read from, the level all XCDs share.  The hand-off of a partial is:
-//   every wave that stored a piece waits until its own vector-memory operations have completed
-//   (wait_own_stores: s_waitcnt vmcnt(0); a write-through store is only counted as complete once
-//   it has been acknowledged by the shared level), THEN the workgroup barrier, THEN one thread's
-//   arrival atomic at that same level.  A workgroup that reads the arrival count as complete
-//   issues its (sc1) merge loads after the atomic has returned, so they reach the shared level
-//   after every store they depend on has been acknowledged there.  No cache-wide write-back or
-//   invalidate is needed because no ordinary cached access ever touches these words in a launch.
-__device__ __forceinline__ void coherent_store(float *p, float v) {
-  __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+// Cross-workgroup traffic inside one launch (split partials, arrival counters) consists of relaxed
+// agent-scope atomics only, which compile to sc1 accesses that are written through to, and read
+// from, the level all XCDs share.  A split partial is handed over WITHOUT any ordering between
+// different words: every 32-bit value travels in one 64-bit word together with the launch's tag
+// (a serial number no earlier launch of this process used), stored and loaded with single 64-bit
+// atomic accesses, so a word is either this launch's value or recognisably stale.  The workgroup
+// that draws the last ticket of a (sequence, KV head) merges: it re-reads a word until its tag is
+// this launch's.  That loop ends: a workgroup draws its ticket only when it is running, it issues its
+// stores without ever waiting for another workgroup, and issued stores become visible.  There is no
+// fence, no wait for store acknowledgements and no cache-wide write-back; no ordinary cached access
+// ever touches these words during a launch.
+__device__ __forceinline__ void tagged_store(uint64_t *p, float v, uint32_t tag) {
+  __hip_atomic_store(p, ((uint64_t)tag << 32) | (uint64_t)__float_as_uint(v), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
-__device__ __forceinline__ float coherent_load(const float *p) {
+__device__ __forceinline__ uint64_t tagged_load(const uint64_t *p) {
   return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
-// The wave's outstanding vector-memory operations (stores included) have all completed when this
-// returns.  Spelt as the instruction itself: a workgroup-scope release fence emits no vector-memory
-// wait on this target, and an agent-scope one adds a write-back of the whole L2.
-__device__ __forceinline__ void wait_own_stores() { asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); }
+// Draw a ticket from a device counter, the answer to be looked at later.  The address is made to look
+// lane-dependent: for a uniform address the compiler rewrites the operation into its wave-aggregated
+// form, whose broadcast of the result waits for the atomic -- and for every load issued before it --
+// on the spot.
+__device__ __forceinline__ uint32_t draw_ticket(uint32_t *counter) {
+  uint32_t zero = 0;
+  asm volatile("" : "+v"(zero));
+  return __hip_atomic_fetch_add(counter + zero, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ __forceinline__ bool tag_is(uint64_t w, uint32_t tag) { return (uint32_t)(w >> 32) == tag; }
+__device__ __forceinline__ float tagged_value(uint64_t w) { return __uint_as_float((uint32_t)w); }
 
 // 2^x by the hardware instruction alone (v_exp_f32, ~1 ulp).  Arguments here are <= 0 up to
 // rounding; results below 2^-126 flush to zero, which is far under what the sums resolve.
@@ -180,7 +179,6 @@ __global__ __launch_bounds__(W * 64, 2) void attend_kernel(const AttendParams p)
   __shared__ uint32_t sm_flag;
   __shared__ int32_t sm_hdr[5];
 
-  DYNTS_STAMP(0);
   const int tid = threadIdx.x;
   const int lane = tid & 63, wave = tid >> 6;
   const int r16 = lane & 15, kg = lane >> 4;
@@ -356,7 +354,7 @@ __global__ __launch_bounds__(W * 64, 2) void attend_kernel(const AttendParams p)
   // trip at the end of the workgroup.
   uint32_t seq_ticket = 0xffffffffu;
   auto seq_checkin = [&]() {
-    if (ATTEND && tid == 0) seq_ticket = atomicAdd(&p.seq_cnt[b], 1u);
+    if (ATTEND && tid == 0) seq_ticket = draw_ticket(&p.seq_cnt[b]);
   };
   auto seq_settle = [&]() {
     if (ATTEND && tid == 0 && seq_ticket == (uint32_t)p.nsplit * p.Hkv - 1) {
@@ -593,26 +591,57 @@ __global__ __launch_bounds__(W * 64, 2) void attend_kernel(const AttendParams p)
     }
   };
 
-  DYNTS_STAMP(1);
-#ifdef DYNTS_TRACE
-  __builtin_amdgcn_s_waitcnt(0);  // development: when has everything the prologue asked for arrived
-  DYNTS_STAMP(2);
-#endif
   if (t < n_vis) tile(t, t + kTile < n_vis ? t + kTile : n_vis, ra);
   seq_settle();
   for (t = ra; t < rb; t += kTile) tile(t, rb, t + kTile);
-  DYNTS_STAMP(3);
-  DYNTS_STAMP(4);
-#ifdef DYNTS_TRACE_WAVES  // development: when each wave left its tile loop (overwrites the phase stamps)
-  if (p.trace && lane == 0)
-    p.trace[(((size_t)blockIdx.z * gridDim.y + blockIdx.y) * gridDim.x + blockIdx.x) * 8 + (wave & 7)] = wall_clock64();
-  __syncthreads();
-  return;
-#endif
 
   if (!ATTEND) return;
+  // with several chunks per unit: draw this workgroup's ticket now, so that the round trip of the atomic
+  // overlaps the combine below.  (The holder of the last ticket merges, whenever it gets there.)
+  uint32_t unit_ticket = 0;
+  if (chunks_vis > 1 && tid == 0) unit_ticket = draw_ticket(&p.unit_cnt[unit]);
   const bool has_partial = split < chunks_now;  // workgroup-uniform; false: the chunk only carried a deferred update
   if (chunks_vis == 1 && !has_partial) return;
+
+  // Merging (several chunks per unit): thread tid owns output elements tid + k * kThreads, in its own partial
+  // and in the merge; chunks are merged kMergeGroup at a time, in chunk order.  Asking for a group means:
+  // every thread requests its elements of the group's partials, and threads 0 .. 16 * kMergeGroup - 1 the
+  // (max, sum) of one (chunk, head) each; this workgroup's own partial never comes from memory.
+  constexpr int NE = (16 * D + kThreads - 1) / kThreads;  // output elements per thread at the largest group size
+  constexpr int kMergeGroup = 4;
+  const int ne = (G * D + kThreads - 1) / kThreads;
+  const size_t ubase = unit * p.nsplit * (size_t)G;
+  uint64_t ask_o[NE][kMergeGroup], ask_m = 0, ask_l = 0;
+  auto ask_group = [&](int s0) {
+#pragma unroll
+    for (int k = 0; k < NE; ++k) {
+      const int idx = tid + k * kThreads;
+#pragma unroll
+      for (int j = 0; j < kMergeGroup; ++j) {
+        const int sj = s0 + j;
+        ask_o[k][j] = (uint64_t)p.tag << 32;  // nothing to wait for
+        if (k < ne && idx < G * D && sj < chunks_now && !(has_partial && sj == split))
+          ask_o[k][j] = tagged_load(&p.part_o[(ubase + (size_t)sj * G + idx / D) * D + idx % D]);
+      }
+    }
+    ask_m = ask_l = (uint64_t)p.tag << 32;
+    if (tid < 16 * kMergeGroup) {
+      const int sj = s0 + (tid >> 4), gg = tid & 15;
+      if (sj < chunks_now && gg < G && !(has_partial && sj == split)) {
+        const uint64_t *src = &p.part_ml[(ubase + (size_t)sj * G + gg) * 2];
+        ask_m = tagged_load(src);
+        ask_l = tagged_load(src + 1);
+      }
+    }
+  };
+  auto group_fresh = [&]() {
+    bool ok = tag_is(ask_m, p.tag) && tag_is(ask_l, p.tag);
+#pragma unroll
+    for (int k = 0; k < NE; ++k)
+#pragma unroll
+      for (int j = 0; j < kMergeGroup; ++j) ok = ok && tag_is(ask_o[k][j], p.tag);
+    return ok;
+  };
 
   // ---- combine the four waves ------------------------------------------------------------
   float *ored = reinterpret_cast<float *>(smem);
@@ -668,97 +697,99 @@ __global__ __launch_bounds__(W * 64, 2) void attend_kernel(const AttendParams p)
         p.mlprev[(orow0 + tid) * 2 + 1] = sm_fin[1][tid];
       }
     }
-    DYNTS_STAMP(7);
     return;
   }
 
-  // ---- several chunks: publish the partial, the last arrival merges ---------------------------
+  // ---- several chunks: publish the partial, the holder of the last ticket merges ----------------
+  float own_o[NE];
+#pragma unroll
+  for (int k = 0; k < NE; ++k) own_o[k] = 0.f;
   if (has_partial) {
     const size_t pbase = (unit * p.nsplit + split) * (size_t)G;
-    for (int idx = tid; idx < G * D; idx += kThreads) {
-      const int gg = idx / D, c = idx % D;
-      float sum = 0.f;
-#pragma unroll
-      for (int w = 0; w < kWaves; ++w) sum += ored[(w * 16 + gg) * OSTRIDE + c];
-      coherent_store(&p.part_o[(pbase + gg) * D + c], sum);
-    }
-    if (tid < G) {
-      coherent_store(&p.part_ml[(pbase + tid) * 2 + 0], sm_fin[0][tid]);
-      coherent_store(&p.part_ml[(pbase + tid) * 2 + 1], sm_fin[1][tid]);
-    }
-  }
-  wait_own_stores();
-  __syncthreads();
-  DYNTS_STAMP(5);
-  if (tid == 0) sm_flag = atomicAdd(&p.unit_cnt[unit], 1u);
-  __syncthreads();
-  DYNTS_STAMP(6);
-  if (sm_flag == (uint32_t)chunks_vis - 1 && tid == 0)
-    __hip_atomic_store(&p.unit_cnt[unit], 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-  if (sm_flag == (uint32_t)chunks_vis - 1 && chunks_now > 0) {
-    // every thread merges its own output elements; the partials of up to four chunks are
-    // requested together so the merge costs one trip to the coherent level, not one per chunk
-    const size_t ubase = unit * p.nsplit * (size_t)G;
-    constexpr int NE = (16 * D + kThreads - 1) / kThreads;  // output elements per thread at the largest group size
-    const int ne = (G * D + kThreads - 1) / kThreads;
-    float m_e[NE], L_e[NE], o_e[NE];
-#pragma unroll
-    for (int k = 0; k < NE; ++k) {
-      m_e[k] = -INFINITY;
-      L_e[k] = 0.f;
-      o_e[k] = 0.f;
-    }
-    for (int s0 = 0; s0 < chunks_now; s0 += 4) {
-      float ms[NE][4], ls[NE][4], os[NE][4];
-#pragma unroll
-      for (int k = 0; k < NE; ++k) {
-        if (k < ne) {
-          int idx = tid + k * kThreads;
-          idx = idx < G * D ? idx : G * D - 1;
-          const int gg = idx / D, c = idx % D;
-#pragma unroll
-          for (int j = 0; j < 4; ++j) {
-            const int sj = s0 + j < chunks_now ? s0 + j : chunks_now - 1;
-            const size_t row = ubase + (size_t)sj * G + gg;
-            ms[k][j] = coherent_load(&p.part_ml[row * 2]);
-            ls[k][j] = coherent_load(&p.part_ml[row * 2 + 1]);
-            os[k][j] = coherent_load(&p.part_o[row * D + c]);
-          }
-        }
-      }
-#pragma unroll
-      for (int k = 0; k < NE; ++k) {
-        if (k < ne) {
-#pragma unroll
-          for (int j = 0; j < 4; ++j) {
-            if (s0 + j < chunks_now) {
-              const float mn = fmaxf(m_e[k], ms[k][j]);
-              const float fa = exp2f(m_e[k] - mn), fb = exp2f(ms[k][j] - mn);
-              L_e[k] = L_e[k] * fa + ls[k][j] * fb;
-              o_e[k] = o_e[k] * fa + os[k][j] * fb;
-              m_e[k] = mn;
-            }
-          }
-        }
-      }
-    }
 #pragma unroll
     for (int k = 0; k < NE; ++k) {
       const int idx = tid + k * kThreads;
       if (k < ne && idx < G * D) {
         const int gg = idx / D, c = idx % D;
-        p.out[(orow0 + gg) * D + c] = o_e[k] / L_e[k];
-        if (c == 0) {
-          if (p.lse) p.lse[orow0 + gg] = (m_e[k] + log2f(L_e[k])) * 0.6931471805599453f;
-          if (p.track) {
-            p.mlprev[(orow0 + gg) * 2] = m_e[k];
-            p.mlprev[(orow0 + gg) * 2 + 1] = L_e[k];
+        float sum = 0.f;
+#pragma unroll
+        for (int w = 0; w < kWaves; ++w) sum += ored[(w * 16 + gg) * OSTRIDE + c];
+        own_o[k] = sum;
+        tagged_store(&p.part_o[(pbase + gg) * D + c], sum, p.tag);
+      }
+    }
+    if (tid < G) {
+      tagged_store(&p.part_ml[(pbase + tid) * 2 + 0], sm_fin[0][tid], p.tag);
+      tagged_store(&p.part_ml[(pbase + tid) * 2 + 1], sm_fin[1][tid], p.tag);
+    }
+  }
+  // the ticket was drawn when this workgroup's first wave left its tile loop; its answer is looked at now
+  if (tid == 0) sm_flag = unit_ticket;
+  __syncthreads();
+  const bool merger = sm_flag == (uint32_t)chunks_vis - 1;
+  if (!merger) return;
+  if (tid == 0) __hip_atomic_store(&p.unit_cnt[unit], 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+  if (chunks_now == 0) return;
+
+  __shared__ float sm_pm[kMergeGroup][16], sm_pl[kMergeGroup][16];
+  float m_e[NE], L_e[NE], o_e[NE];
+#pragma unroll
+  for (int k = 0; k < NE; ++k) {
+    m_e[k] = -INFINITY;
+    L_e[k] = 0.f;
+    o_e[k] = 0.f;
+  }
+#ifdef EXP_MERGER_WAITS
+  asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+#endif
+  for (int s0 = 0; s0 < chunks_now; s0 += kMergeGroup) {
+    ask_group(s0);
+    while (!group_fresh()) ask_group(s0);  // a word that is not this launch's yet is on its way: ask again
+    if (tid < 16 * kMergeGroup) {
+      const int j = tid >> 4, gg = tid & 15, sj = s0 + j;
+      if (sj < chunks_now && gg < G) {
+        const bool mine = has_partial && sj == split;
+        sm_pm[j][gg] = mine ? sm_fin[0][gg] : tagged_value(ask_m);
+        sm_pl[j][gg] = mine ? sm_fin[1][gg] : tagged_value(ask_l);
+      }
+    }
+    __syncthreads();
+#pragma unroll
+    for (int k = 0; k < NE; ++k) {
+      const int idx = tid + k * kThreads;
+      if (k < ne && idx < G * D) {
+        const int gg = idx / D;
+#pragma unroll
+        for (int j = 0; j < kMergeGroup; ++j) {
+          if (s0 + j < chunks_now) {
+            const float ms = sm_pm[j][gg], ls = sm_pl[j][gg];
+            const float ov = (has_partial && s0 + j == split) ? own_o[k] : tagged_value(ask_o[k][j]);
+            const float mn = fmaxf(m_e[k], ms);  // finite: a chunk that has a partial has attended a slot
+            const float fa = fast_exp2(m_e[k] - mn), fb = fast_exp2(ms - mn);
+            L_e[k] = L_e[k] * fa + ls * fb;
+            o_e[k] = o_e[k] * fa + ov * fb;
+            m_e[k] = mn;
           }
         }
       }
     }
+    if (s0 + kMergeGroup < chunks_now) __syncthreads();  // the statistics' LDS is written again
   }
-  DYNTS_STAMP(7);
+#pragma unroll
+  for (int k = 0; k < NE; ++k) {
+    const int idx = tid + k * kThreads;
+    if (k < ne && idx < G * D) {
+      const int gg = idx / D, c = idx % D;
+      p.out[(orow0 + gg) * D + c] = o_e[k] / L_e[k];
+      if (c == 0) {
+        if (p.lse) p.lse[orow0 + gg] = (m_e[k] + log2f(L_e[k])) * 0.6931471805599453f;
+        if (p.track) {
+          p.mlprev[(orow0 + gg) * 2] = m_e[k];
+          p.mlprev[(orow0 + gg) * 2 + 1] = L_e[k];
+        }
+      }
+    }
+  }
 }
 
 }  // namespace dynts

@@ -5,6 +5,7 @@
 #include <hip/hip_ext.h>
 #include <hip/hip_runtime.h>
 
+#include <atomic>
 #include <cmath>
 #include <cstdlib>
 #include <cstring>
@@ -53,20 +54,12 @@ int check_config(const dynts_config *c) {
 // multiples of the workgroup's tile quantum.  The aim is about one 8-wave workgroup per compute
 // unit: few enough that every wave loops over many tiles with its loads in flight, and that
 // the split partials stay small.
-Plan make_plan(const dynts_config &c) {
+Plan make_plan(const dynts_config &c, int target_wgs, int waves) {
   Plan p;
   p.G = c.n_q_heads / c.n_kv_heads;
   const long long units = (long long)c.batch * c.n_kv_heads;
-  long long target = 256;  // workgroups wanted (256 compute units)
-  p.waves = 8;
-  if (const char *e = std::getenv("DYNTS_TARGET_WGS")) {
-    long long v = std::atoll(e);
-    if (v > 0) target = v;
-  }
-  if (const char *e = std::getenv("DYNTS_WAVES")) {
-    int v = std::atoi(e);
-    if (v == 4 || v == 8) p.waves = v;
-  }
+  const long long target = target_wgs > 0 ? target_wgs : 256;  // workgroups wanted (256 compute units)
+  p.waves = waves == 4 ? 4 : 8;
   const int quantum = p.waves * dynts::kTile;
   const int quanta = (c.capacity + quantum - 1) / quantum;
   long long want = (target + units / 2) / units;
@@ -77,8 +70,8 @@ Plan make_plan(const dynts_config &c) {
   p.nsplit = (c.capacity + p.chunk - 1) / p.chunk;
   const size_t rows = (size_t)units * p.nsplit * p.G;
   size_t off = 0;
-  p.off_part_o = off;  off = align_up(off + rows * c.head_dim * sizeof(float));
-  p.off_part_ml = off; off = align_up(off + rows * 2 * sizeof(float));
+  p.off_part_o = off;  off = align_up(off + rows * c.head_dim * sizeof(uint64_t));  // value + tag per word
+  p.off_part_ml = off; off = align_up(off + rows * 2 * sizeof(uint64_t));
   p.off_unit_cnt = off; off = align_up(off + (size_t)units * sizeof(uint32_t));
   p.off_seq_cnt = off; off = align_up(off + (size_t)c.batch * sizeof(uint32_t));
   const size_t LB = (size_t)c.n_layers * c.batch;
@@ -105,7 +98,6 @@ struct dynts_ctx {
   hipEvent_t ev_start = nullptr, ev_stop = nullptr;
   std::vector<hipEvent_t> ev_list_start, ev_list_stop;  // one pair per coming attend launch
   size_t ev_list_next = 0;
-  unsigned long long *trace = nullptr;
   // paged layout (dynts_bind_paged): K and V above are the page pools
   bool paged = false;
   int32_t *block_table = nullptr, *free_stack = nullptr, *free_top = nullptr;
@@ -115,6 +107,16 @@ struct dynts_ctx {
 namespace {
 
 int launch_status() { return hipGetLastError() == hipSuccess ? DYNTS_OK : DYNTS_EHIP; }
+
+// Serial number of an attend launch: the tag its split partials carry.  One counter for the whole
+// process, so that two contexts which share scratch memory can never mistake each other's words for
+// their own; 0 is skipped (zero-filled scratch must read as stale).
+uint32_t next_launch_tag() {
+  static std::atomic<uint32_t> serial{0};
+  uint32_t t = serial.fetch_add(1, std::memory_order_relaxed) + 1;
+  if (t == 0) t = serial.fetch_add(1, std::memory_order_relaxed) + 1;
+  return t;
+}
 
 int check_call(const dynts_ctx *ctx, int32_t layer) {
   if (!ctx) return DYNTS_ENULL;
@@ -194,14 +196,14 @@ int run_attend(dynts_ctx *ctx, int layer, const uint16_t *q, const uint16_t *k_n
   p.q = q; p.k_new = k_new; p.v_new = v_new; p.s_new = s_new; p.active = active;
   p.out = out; p.lse = lse;
   p.qprev = lv.qprev; p.qnext = lv.qnext; p.mlprev = lv.mlprev; p.nprev = lv.nprev;
-  p.part_o = reinterpret_cast<float *>(ctx->ws + pl.off_part_o);
-  p.part_ml = reinterpret_cast<float *>(ctx->ws + pl.off_part_ml);
+  p.part_o = reinterpret_cast<uint64_t *>(ctx->ws + pl.off_part_o);
+  p.part_ml = reinterpret_cast<uint64_t *>(ctx->ws + pl.off_part_ml);
+  p.tag = next_launch_tag();
   p.unit_cnt = reinterpret_cast<uint32_t *>(ctx->ws + pl.off_unit_cnt);
   p.seq_cnt = reinterpret_cast<uint32_t *>(ctx->ws + pl.off_seq_cnt);
   p.status = ctx->status;
   p.Nb = c.batch; p.Hq = c.n_q_heads; p.Hkv = c.n_kv_heads; p.G = pl.G; p.cap = c.capacity;
   p.nsplit = pl.nsplit; p.track = track ? 1 : 0; p.scale_log2 = ctx->scale_log2;
-  p.trace = ctx->trace;
   p.block_table = lv.block_table; p.block_table_w = lv.block_table; p.free_stack = ctx->free_stack;
   p.free_top = ctx->free_top; p.max_pages = ctx->max_pages; p.n_pages = ctx->n_pages;
 
@@ -265,7 +267,7 @@ MlpScratch mlp_scratch(const dynts_predictor *w, int batch, const MlpPlan &l1, c
   sc.off_p2 = off;
   off += align_up((size_t)l2.nsplit * batch * w->m2 * sizeof(float));
   sc.off_part = off;
-  off += align_up((size_t)batch * ((w->m2 + 255) / 256) * sizeof(float));
+  off += align_up((size_t)batch * ((w->m2 + 255) / 256) * sizeof(uint64_t));  // tagged words
   sc.off_cnt = off;
   off += align_up((size_t)batch * sizeof(uint32_t));
   sc.total = off;
@@ -313,7 +315,7 @@ int dynts_create(const dynts_config *cfg, dynts_ctx **out) {
   dynts_ctx *ctx = new (std::nothrow) dynts_ctx();
   if (!ctx) return DYNTS_EINVAL;
   ctx->cfg = *cfg;
-  ctx->plan = make_plan(*cfg);
+  ctx->plan = make_plan(*cfg, 0, 0);
   const float scale = cfg->softmax_scale > 0.f ? cfg->softmax_scale : 1.0f / std::sqrt((float)cfg->head_dim);
   ctx->scale_log2 = scale * 1.4426950408889634f;
   ctx->pending.assign((size_t)cfg->n_layers, 0);
@@ -328,9 +330,20 @@ int dynts_destroy(dynts_ctx *ctx) {
   return DYNTS_OK;
 }
 
+int dynts_set_launch_shape(dynts_ctx *ctx, int32_t target_workgroups, int32_t waves_per_workgroup) {
+  if (!ctx) return DYNTS_ENULL;
+  if (target_workgroups < 0 || (waves_per_workgroup != 0 && waves_per_workgroup != 4 && waves_per_workgroup != 8))
+    return DYNTS_EINVAL;
+  ctx->plan = make_plan(ctx->cfg, target_workgroups, waves_per_workgroup);
+  ctx->bound = false;  // the workspace layout changed
+  return DYNTS_OK;
+}
+
+size_t dynts_ctx_workspace_bytes(const dynts_ctx *ctx) { return ctx ? ctx->plan.bytes : 0; }
+
 size_t dynts_workspace_bytes(const dynts_config *cfg) {
   if (check_config(cfg) != DYNTS_OK) return 0;
-  return make_plan(*cfg).bytes;
+  return make_plan(*cfg, 0, 0).bytes;
 }
 
 int dynts_bind(dynts_ctx *ctx, uint16_t *K, uint16_t *V, float *S, int32_t *pos, int32_t *seq_len,
@@ -526,15 +539,6 @@ int dynts_set_kernel_events(dynts_ctx *ctx, void *start, void *stop) {
   return DYNTS_OK;
 }
 
-#ifdef DYNTS_TRACE
-// Development builds only: 8 wall-clock stamps per workgroup of the next attend launches.
-int dynts_set_trace(dynts_ctx *ctx, unsigned long long *buf) {
-  if (!ctx) return DYNTS_ENULL;
-  ctx->trace = buf;
-  return DYNTS_OK;
-}
-#endif
-
 int dynts_set_kernel_event_list(dynts_ctx *ctx, void *const *starts, void *const *stops, int32_t n) {
   if (!ctx) return DYNTS_ENULL;
   if (n < 0) return DYNTS_EINVAL;
@@ -654,7 +658,7 @@ int dynts_predict_scores(const dynts_predictor *w, const uint16_t *h, int32_t ba
   else launch_mlp_gemm<2, false>(g2, l2, st, nullptr, nullptr);
   hipExtLaunchKernelGGL(dynts::mlp_reduce_dot_kernel, dim3((w->m2 + 255) / 256, batch), dim3(256), 0, st, nullptr,
                         static_cast<hipEvent_t>(stop), 0, P2, w->b2, l2.nsplit, batch, w->m2, w->activation, w->w3,
-                        w->b3, reinterpret_cast<float *>(base + sc.off_part),
+                        w->b3, reinterpret_cast<uint64_t *>(base + sc.off_part), next_launch_tag(),
                         reinterpret_cast<uint32_t *>(base + sc.off_cnt), s_out, n_rep);
   return launch_status();
 }

@@ -202,11 +202,14 @@ __global__ __launch_bounds__(256) void mlp_reduce_act_kernel(const float *P, con
 
 // s[b] = w3 . act(sum over splits of P[.][b][:] + bias) + b3, written n_rep times.
 // grid (ceil(m / 256), Nb), 256 threads: a workgroup takes 256 features of one sequence and leaves its part of
-// the dot product in part[b][blockIdx.x]; the last workgroup of a sequence to arrive (device counter) adds the
-// parts in index order, so the result does not depend on the arrival order.
+// the dot product in part[b][blockIdx.x] as a tagged word (value + this call's serial number in one 64-bit
+// atomic store, as the attention kernel's split partials); the workgroup that draws the last ticket of a
+// sequence adds the parts in index order, re-reading a word until it carries this call's tag, so the result
+// does not depend on the arrival order and no store has to be waited for.
 __global__ __launch_bounds__(256) void mlp_reduce_dot_kernel(const float *P, const float *bias, int nsplit, int Nb,
                                                              int m, int act, const uint16_t *w3, const float *b3,
-                                                             float *part, uint32_t *row_cnt, float *s_out, int n_rep) {
+                                                             uint64_t *part, uint32_t tag, uint32_t *row_cnt,
+                                                             float *s_out, int n_rep) {
   __shared__ float red[4];
   __shared__ int is_last;
   const int b = blockIdx.y, tid = threadIdx.x, o = blockIdx.x * 256 + tid;
@@ -222,15 +225,19 @@ __global__ __launch_bounds__(256) void mlp_reduce_dot_kernel(const float *P, con
   if ((tid & 63) == 0) red[tid >> 6] = t;
   __syncthreads();
   if (tid == 0) {
-    coherent_store(part + (size_t)b * gridDim.x + blockIdx.x, (red[0] + red[1]) + (red[2] + red[3]));
-    wait_own_stores();
+    tagged_store(part + (size_t)b * gridDim.x + blockIdx.x, (red[0] + red[1]) + (red[2] + red[3]), tag);
     is_last = atomicAdd(row_cnt + b, 1u) == gridDim.x - 1;
   }
   __syncthreads();
   if (!is_last) return;
   if (tid < n_rep) {
     float tot = 0.f;
-    for (unsigned k = 0; k < gridDim.x; ++k) tot += coherent_load(part + (size_t)b * gridDim.x + k);
+    for (unsigned k = 0; k < gridDim.x; ++k) {
+      uint64_t w;
+      do w = tagged_load(part + (size_t)b * gridDim.x + k);
+      while (!tag_is(w, tag));
+      tot += tagged_value(w);
+    }
     s_out[(size_t)b * n_rep + tid] = tot + (b3 ? b3[0] : 0.f);
   }
 }

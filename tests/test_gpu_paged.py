@@ -42,16 +42,14 @@ def _check_pages(cache):
 @pytest.mark.parametrize("one_workgroup", [False, True])
 @pytest.mark.parametrize("mode", ["unfused", "fused", "step"])
 @pytest.mark.parametrize("d,Hq,Hkv", [(64, 8, 2), (128, 28, 4)])
-def test_trajectory_paged(B, mode, d, Hq, Hkv, one_workgroup, monkeypatch):
+def test_trajectory_paged(B, mode, d, Hq, Hkv, one_workgroup):
     """Several pages per unit, ragged prompts, evictions that free pages, a sequence that finishes early.
     one_workgroup: a single workgroup per unit, so that every wave walks a range of tiles behind its first one
     (the launch shape of the large workloads) instead of one tile each."""
-    if one_workgroup:
-        monkeypatch.setenv("DYNTS_TARGET_WGS", "1")
     rng = np.random.default_rng(300 + d + Hq)
     Nb, M_max, budget, window, E, T = 3, 37, 150, 19, 91, 420
     cap = M_max + budget + window + E
-    cache = B.PagedCache(1, Nb, Hq, Hkv, d, cap, budget, window, E)
+    cache = B.PagedCache(1, Nb, Hq, Hkv, d, cap, budget, window, E, launch_shape=(1, 8) if one_workgroup else None)
     o = orc.OracleLayer(Nb, Hq, Hkv, d, cap, budget, window, E)
     sbs = SideBySide(B, cache, 0, o, mode)
     sbs.prefill(_bf16(rng, Nb, Hkv, M_max, d), _bf16(rng, Nb, Hkv, M_max, d), [37, 5, 20])

@@ -21,9 +21,10 @@ def _bf16(rng, *shape, scale=1.0):
     return torch.from_numpy(rng.standard_normal(shape).astype(np.float32) * scale).to(torch.bfloat16)
 
 
-def _pair(B, Nb, Hq, Hkv, d, M_max, budget, window, E, mode, external=False, scale=0.0):
+def _pair(B, Nb, Hq, Hkv, d, M_max, budget, window, E, mode, external=False, scale=0.0, launch_shape=None):
     cap = M_max + budget + window + E
-    cache = B.Cache(1, Nb, Hq, Hkv, d, cap, budget, window, E, softmax_scale=scale, external_scores=external)
+    cache = B.Cache(1, Nb, Hq, Hkv, d, cap, budget, window, E, softmax_scale=scale, external_scores=external,
+                    launch_shape=launch_shape)
     o = orc.OracleLayer(Nb, Hq, Hkv, d, cap, budget, window, E,
                         softmax_scale=scale if scale else None, external_scores=external)
     return SideBySide(B, cache, 0, o, mode), cap
@@ -53,16 +54,14 @@ def test_trajectory_small(B, mode, d, Hq, Hkv):
     assert int(sbs.c.seq_len[0, 1].item()) == sbs.o.seq_len[1]
 
 
-@pytest.mark.parametrize("waves", ["4", "8"])
+@pytest.mark.parametrize("waves", [4, 8])
 @pytest.mark.parametrize("d,Hq,Hkv", [(64, 8, 2), (128, 28, 4)])
-def test_trajectory_single_workgroup(B, d, Hq, Hkv, waves, monkeypatch):
+def test_trajectory_single_workgroup(B, d, Hq, Hkv, waves):
     """One workgroup per (sequence, KV head), 4 or 8 waves: every wave walks a ragged range of slots behind its
     first tile, the launch shape of the large workloads, here at a size the oracle replays step by step."""
-    monkeypatch.setenv("DYNTS_TARGET_WGS", "1")
-    monkeypatch.setenv("DYNTS_WAVES", waves)
     rng = np.random.default_rng(500 + d + Hq)
     Nb, M_max, budget, window, E, T = 2, 41, 330, 23, 57, 560
-    sbs, cap = _pair(B, Nb, Hq, Hkv, d, M_max, budget, window, E, "step")
+    sbs, cap = _pair(B, Nb, Hq, Hkv, d, M_max, budget, window, E, "step", launch_shape=(1, waves))
     sbs.prefill(_bf16(rng, Nb, Hkv, M_max, d), _bf16(rng, Nb, Hkv, M_max, d), [41, 7])
     for t in range(1, T + 1):
         sbs.step(_bf16(rng, Nb, Hq, d, scale=1.5), _bf16(rng, Nb, Hkv, d), _bf16(rng, Nb, Hkv, d),
