@@ -199,6 +199,9 @@ int run_attend(dynts_ctx *ctx, int layer, const uint16_t *q, const uint16_t *k_n
   p.part_o = reinterpret_cast<uint64_t *>(ctx->ws + pl.off_part_o);
   p.part_ml = reinterpret_cast<uint64_t *>(ctx->ws + pl.off_part_ml);
   p.tag = next_launch_tag();
+  // score writes: tile by tile while the layer's K and V fit the memory-side cache (256 MB), in bursts beyond
+  const double kv_bytes = 4.0 * c.batch * c.n_kv_heads * (double)c.capacity * c.head_dim;
+  p.score_tiles = kv_bytes > 192e6 ? 16 : 1;
   p.unit_cnt = reinterpret_cast<uint32_t *>(ctx->ws + pl.off_unit_cnt);
   p.seq_cnt = reinterpret_cast<uint32_t *>(ctx->ws + pl.off_seq_cnt);
   p.status = ctx->status;
