@@ -157,6 +157,30 @@ int dynts_decode_step(dynts_ctx *ctx, int32_t layer, const uint16_t *q, const ui
                       const uint16_t *v_new, const float *s_new, const uint8_t *active,
                       float *out, float *lse, void *stream);
 
+/* dynts_decode_step for callers that cannot allocate device memory and want to hand over as little as possible
+ * (code under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc): the same step, but
+ * the launch's scratch -- the split partials and the ticket counters, i.e. everything in the workspace that
+ * does not have to survive the call -- lives in an array that is part of the library's code object on each
+ * GPU (DYNTS_STATIC_SCRATCH_BYTES = 8 MiB, held until the process ends) instead of the head of the
+ * bound workspace.  The call allocates nothing and frees nothing, on the host side of HIP or the device side.
+ * The state that carries over between steps (saved queries and softmax statistics of the deferred score
+ * update) stays in the bound workspace, so this call and dynts_decode_step may be mixed freely on a context.
+ *  - DYNTS_EWORKSPACE if the context's shape needs more scratch than the array holds: the partials take
+ *    batch * n_kv_heads * chunks * group * (head_dim + 2) * 8 bytes of its upper 7 MiB (chunks being what
+ *    dynts_set_launch_shape describes; with the default shape 2 MiB on the 32-sequence Qwen-shaped workload,
+ *    nothing once there are as many (sequence, KV head) units as compute units), the counters 4 bytes per
+ *    unit and per sequence of 512 KiB each.  Nothing is launched then.
+ *  - All calls on one GPU share that GPU's array, from every context and stream: calls that may overlap in
+ *    time on one GPU race with each other -- keep them on one stream or order them with events.  (Calls that
+ *    are stream-ordered leave the array as the next one needs it, whatever its shape: counters live in a part
+ *    of the array that holds nothing else and are back at zero when a launch ends, partials are tagged with
+ *    a serial number that no other launch of the process uses.)
+ *  - The first call on a GPU looks the array up and clears it with a small kernel on the caller's stream. */
+#define DYNTS_STATIC_SCRATCH_BYTES (8u << 20)
+int dynts_decode_step_static(dynts_ctx *ctx, int32_t layer, const uint16_t *q, const uint16_t *k_new,
+                             const uint16_t *v_new, const float *s_new, const uint8_t *active,
+                             float *out, float *lse, void *stream);
+
 /* KV-cache selection (Sec. 4.2, third paragraph): for every sequence with trigger[b] != 0
  * (uint8 [Nb], NULL = all) and every KV head keep all question slots, the last `window`
  * slots, and of the slots between them the k_keep with the highest score (ties: lower

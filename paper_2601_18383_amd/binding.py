@@ -25,6 +25,7 @@ EXPORTS = [
     "dynts_score_block_scratch_bytes", "dynts_score_block",
     "dynts_predict_scratch_bytes", "dynts_predict_scores", "dynts_predictor_pack", "dynts_bind_paged",
     "dynts_set_launch_shape", "dynts_ctx_workspace_bytes",
+    "dynts_decode_step_static",
 ]
 
 
@@ -69,6 +70,7 @@ def _load():
     lib.dynts_update_scores.argtypes = [vp, i32, vp]
     lib.dynts_decode_attend_update.argtypes = [vp, i32, vp, vp, vp, vp, vp]
     lib.dynts_decode_step.argtypes = [vp, i32, vp, vp, vp, vp, vp, vp, vp, vp]
+    lib.dynts_decode_step_static.argtypes = [vp, i32, vp, vp, vp, vp, vp, vp, vp, vp]
     lib.dynts_select_evict.argtypes = [vp, i32, vp, i32, vp, i32, vp, vp]
     lib.dynts_compact.argtypes = [vp, i32, vp, vp, i32, vp, vp]
     lib.dynts_decode_loop.argtypes = [vp, i32, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp, vp, vp]
@@ -205,6 +207,16 @@ def dynts_decode_step(ctx, layer, q, k_new, v_new, out, s_new=None, active=None,
                                  _ptr(v_new, torch.bfloat16), _ptr(s_new, torch.float32),
                                  _ptr(active, torch.uint8), _ptr(out, torch.float32), _ptr(lse, torch.float32),
                                  _stream(stream)), "dynts_decode_step")
+
+
+def dynts_decode_step_static(ctx, layer, q, k_new, v_new, out, s_new=None, active=None, lse=None, stream=None):
+    _check(lib.dynts_decode_step_static(ctx, layer, _ptr(q, torch.bfloat16), _ptr(k_new, torch.bfloat16),
+                                        _ptr(v_new, torch.bfloat16), _ptr(s_new, torch.float32),
+                                        _ptr(active, torch.uint8), _ptr(out, torch.float32), _ptr(lse, torch.float32),
+                                        _stream(stream)), "dynts_decode_step_static")
+
+
+DYNTS_STATIC_SCRATCH_BYTES = 8 << 20
 
 
 def dynts_select_evict(ctx, layer, keep_idx, new_len, k_keep=-1, trigger=None, stream=None):

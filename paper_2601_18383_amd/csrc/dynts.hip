@@ -9,6 +9,7 @@
 #include <cmath>
 #include <cstdlib>
 #include <cstring>
+#include <mutex>
 #include <new>
 #include <vector>
 
@@ -181,12 +182,29 @@ void launch_partial_d(const dynts::AttendParams &p, dim3 grid, hipStream_t st, h
   return launch_partial<D, W, true, false, false>(p, grid, st, e0, e1);
 }
 
+// scratch of one attend launch: split partials (tagged words) and ticket counters (zero between launches)
+struct Transient {
+  uint64_t *part_o, *part_ml;
+  uint32_t *unit_cnt, *seq_cnt;
+};
+
 // attend (optionally with fused append) and/or the deferred score update of one layer
 int run_attend(dynts_ctx *ctx, int layer, const uint16_t *q, const uint16_t *k_new, const uint16_t *v_new,
                const float *s_new, const uint8_t *active, float *out, float *lse, bool attend,
-               bool apply_pending, bool append, hipStream_t st) {
+               bool apply_pending, bool append, hipStream_t st, const Transient *transient = nullptr) {
+  // transient: where the split partials and the counters of this launch live (default: the head of the
+  // workspace); what must survive from one step to the next is always in the workspace
   const dynts_config &c = ctx->cfg;
   const Plan &pl = ctx->plan;
+  Transient tr;
+  if (transient) {
+    tr = *transient;
+  } else {
+    tr.part_o = reinterpret_cast<uint64_t *>(ctx->ws + pl.off_part_o);
+    tr.part_ml = reinterpret_cast<uint64_t *>(ctx->ws + pl.off_part_ml);
+    tr.unit_cnt = reinterpret_cast<uint32_t *>(ctx->ws + pl.off_unit_cnt);
+    tr.seq_cnt = reinterpret_cast<uint32_t *>(ctx->ws + pl.off_seq_cnt);
+  }
   const LayerView lv = layer_view(ctx, layer);
   const bool track = c.score_mode == DYNTS_SCORE_ACCUMULATE;
 
@@ -196,14 +214,14 @@ int run_attend(dynts_ctx *ctx, int layer, const uint16_t *q, const uint16_t *k_n
   p.q = q; p.k_new = k_new; p.v_new = v_new; p.s_new = s_new; p.active = active;
   p.out = out; p.lse = lse;
   p.qprev = lv.qprev; p.qnext = lv.qnext; p.mlprev = lv.mlprev; p.nprev = lv.nprev;
-  p.part_o = reinterpret_cast<uint64_t *>(ctx->ws + pl.off_part_o);
-  p.part_ml = reinterpret_cast<uint64_t *>(ctx->ws + pl.off_part_ml);
+  p.part_o = tr.part_o;
+  p.part_ml = tr.part_ml;
   p.tag = next_launch_tag();
   // score writes: tile by tile while the layer's K and V fit the memory-side cache (256 MB), in bursts beyond
   const double kv_bytes = 4.0 * c.batch * c.n_kv_heads * (double)c.capacity * c.head_dim;
   p.score_tiles = kv_bytes > 192e6 ? 16 : 1;
-  p.unit_cnt = reinterpret_cast<uint32_t *>(ctx->ws + pl.off_unit_cnt);
-  p.seq_cnt = reinterpret_cast<uint32_t *>(ctx->ws + pl.off_seq_cnt);
+  p.unit_cnt = tr.unit_cnt;
+  p.seq_cnt = tr.seq_cnt;
   p.status = ctx->status;
   p.Nb = c.batch; p.Hq = c.n_q_heads; p.Hkv = c.n_kv_heads; p.G = pl.G; p.cap = c.capacity;
   p.nsplit = pl.nsplit; p.track = track ? 1 : 0; p.scale_log2 = ctx->scale_log2;
@@ -287,6 +305,39 @@ void launch_mlp_gemm(const dynts::MlpGemmParams &p, const MlpPlan &pl, hipStream
     case 4: hipExtLaunchKernelGGL((dynts::mlp_gemm_kernel<4, PARTS, PACKED>), grid, block, 0, st, e0, e1, 0, p); break;
     default: hipExtLaunchKernelGGL((dynts::mlp_gemm_kernel<8, PARTS, PACKED>), grid, block, 0, st, e0, e1, 0, p); break;
   }
+}
+
+// ---- scratch that nobody allocates (dynts_decode_step_static) ----------------------------------------
+// One array per GPU, part of the loaded code object, alive until the process ends.  Host code never uses the
+// array's name as an address: it asks the runtime for the device address once per device and keeps it.
+constexpr size_t kStaticScratchBytes = DYNTS_STATIC_SCRATCH_BYTES;
+constexpr size_t kStaticCounters = size_t(1) << 20;  // the first MiB holds counters only
+static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
+
+__global__ void static_scratch_clear_kernel(uint32_t *words, size_t n) {
+  for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += (size_t)gridDim.x * blockDim.x) words[i] = 0u;
+}
+
+constexpr int kMaxDevices = 64;
+std::mutex static_scratch_mutex;
+unsigned char *static_scratch_ptr[kMaxDevices] = {};
+
+// Device address of this GPU's array (the current device), looked up and cleared on first use.  nullptr on error.
+unsigned char *static_scratch(hipStream_t st) {
+  int dev = -1;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return nullptr;
+  std::lock_guard<std::mutex> lock(static_scratch_mutex);
+  if (!static_scratch_ptr[dev]) {
+    unsigned char *ptr = nullptr;
+    if (hipGetSymbolAddress(reinterpret_cast<void **>(&ptr), HIP_SYMBOL(scratch)) != hipSuccess || !ptr) return nullptr;
+    // counters must start at zero (launches leave them at zero afterwards); the whole array, once, with a
+    // fill kernel on the caller's stream -- stream order puts it before the first launch that uses the array
+    hipLaunchKernelGGL(static_scratch_clear_kernel, dim3(256), dim3(256), 0, st, reinterpret_cast<uint32_t *>(ptr),
+                       kStaticScratchBytes / sizeof(uint32_t));
+    if (hipGetLastError() != hipSuccess) return nullptr;
+    static_scratch_ptr[dev] = ptr;
+  }
+  return static_scratch_ptr[dev];
 }
 
 }  // namespace
@@ -481,6 +532,41 @@ int dynts_decode_step(dynts_ctx *ctx, int32_t layer, const uint16_t *q, const ui
     return DYNTS_EINVAL;
   rc = run_attend(ctx, layer, q, k_new, v_new, ext ? s_new : nullptr, active, out, lse, true,
                   ctx->pending[layer] != 0, true, static_cast<hipStream_t>(stream));
+  if (rc == DYNTS_OK) ctx->pending[layer] = !ext;
+  return rc;
+}
+
+int dynts_decode_step_static(dynts_ctx *ctx, int32_t layer, const uint16_t *q, const uint16_t *k_new,
+                             const uint16_t *v_new, const float *s_new, const uint8_t *active, float *out, float *lse,
+                             void *stream) {
+  int rc = check_call(ctx, layer);
+  if (rc != DYNTS_OK) return rc;
+  if (!q || !out || !k_new || !v_new) return DYNTS_ENULL;
+  const bool ext = ctx->cfg.score_mode == DYNTS_SCORE_EXTERNAL;
+  if (ext && !s_new) return DYNTS_ENULL;
+  if ((reinterpret_cast<uintptr_t>(q) | reinterpret_cast<uintptr_t>(k_new) | reinterpret_cast<uintptr_t>(v_new)) % 16)
+    return DYNTS_EINVAL;
+  // Layout of the static array, the same for every context so that what one call leaves fits the next:
+  //   [0, 512 KiB)      ticket counters of the (sequence, KV head) units -- every launch leaves them at zero
+  //   [512 KiB, 1 MiB)  check-in counters of the sequences               -- likewise
+  //   [1 MiB, 8 MiB)    split partials: tagged words, a stale one is recognised whoever wrote it
+  const dynts_config &c = ctx->cfg;
+  const Plan &pl = ctx->plan;
+  const size_t units = (size_t)c.batch * c.n_kv_heads, rows = units * pl.nsplit * pl.G;
+  const size_t part_o_bytes = align_up(rows * c.head_dim * sizeof(uint64_t)), part_ml_bytes = rows * 2 * sizeof(uint64_t);
+  if (units * sizeof(uint32_t) > kStaticCounters / 2 || (size_t)c.batch * sizeof(uint32_t) > kStaticCounters / 2 ||
+      part_o_bytes + part_ml_bytes > kStaticScratchBytes - kStaticCounters)
+    return DYNTS_EWORKSPACE;
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  unsigned char *base = static_scratch(st);
+  if (!base) return DYNTS_EHIP;
+  Transient tr;
+  tr.unit_cnt = reinterpret_cast<uint32_t *>(base);
+  tr.seq_cnt = reinterpret_cast<uint32_t *>(base + kStaticCounters / 2);
+  tr.part_o = reinterpret_cast<uint64_t *>(base + kStaticCounters);
+  tr.part_ml = reinterpret_cast<uint64_t *>(base + kStaticCounters + part_o_bytes);
+  rc = run_attend(ctx, layer, q, k_new, v_new, ext ? s_new : nullptr, active, out, lse, true,
+                  ctx->pending[layer] != 0, true, st, &tr);
   if (rc == DYNTS_OK) ctx->pending[layer] = !ext;
   return rc;
 }
