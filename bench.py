@@ -141,6 +141,127 @@ def read_stream_rates(B, nbytes, dev):
     return {k: round(v, 1) for k, v in best.items()}
 
 
+def time_periods(B, cache, gen, wl, lengths, out, t0, dev, n_periods=5, kernel_events=0, period=None):
+    """n_periods windows of evict_every whole steps each, starting at decode step t0 + 1 (t0 a step right after a
+    trigger, so each window ends on its one trigger), timed with events on the launch stream and no host
+    synchronisation in between.  Returns the full_period block; with kernel_events > 0 also the average
+    duration of that many attend launches (dispatch-attached events) and their algorithmic bytes."""
+    import torch
+    E, L = period or wl.evict_every, wl.n_layers
+    n = E * n_periods
+    q, k, v, s = make_pools(gen, wl, t0, n, dev)
+    flags = evict_flags(wl, t0, n)
+    act, act_host = active_pool(lengths, t0, n, dev)
+    marks = [torch.cuda.Event(enable_timing=True) for _ in range(n_periods + 1)]
+    ev = None
+    if kernel_events:
+        kernel_events = min(kernel_events, n * L)
+        ev = HipEvents(kernel_events)
+        B.dynts_set_kernel_event_list(cache.ctx, [a for a, _ in ev.pairs], [b for _, b in ev.pairs])
+    torch.cuda.synchronize()
+    marks[0].record()
+    for i in range(n_periods):
+        a, b = i * E, (i + 1) * E
+        B.dynts_decode_loop(cache.ctx, E, q[a:b], k[a:b], v[a:b], out, cache.keep_idx, cache.new_len,
+                            s_new=s[a:b] if s is not None else None, active=act[a:b] if act is not None else None,
+                            evict_steps=flags[a:b], trigger=act[a:b] if act is not None else None)
+        marks[i + 1].record()
+    torch.cuda.synchronize()
+    if ev:
+        B.dynts_set_kernel_event_list(cache.ctx, [], [])
+    ms = sorted(marks[i].elapsed_time(marks[i + 1]) / E for i in range(n_periods))
+    med = ms[len(ms) // 2]
+    act_counts = [int(act_host[i].sum()) for i in range(n)]
+    step_bytes = sum(algorithmic_bytes(wl, [cache_len_before_step(wl, t0 + 1 + i)] * act_counts[i], act_counts[i])
+                     for i in range(n)) * L / n
+    r = {"windows": n_periods, "steps_each": E, "evictions": int(flags.sum()), "first_step": t0 + 1,
+         "ms_per_step_median": round(med, 5), "ms_per_step_min": round(ms[0], 5), "ms_per_step_max": round(ms[-1], 5),
+         "steps_per_s": round(1e3 / med, 2), "algorithmic_GBps": round(step_bytes / (med * 1e-3) / 1e9, 1)}
+    if ev:
+        k_ms = [ev.elapsed_ms(i) for i in range(kernel_events)]
+        ev.close()
+        # launches are step-major, layer-minor: launch j belongs to step j // L
+        kb = [algorithmic_bytes(wl, [cache_len_before_step(wl, t0 + 1 + j // L)] * act_counts[j // L], act_counts[j // L])
+              for j in range(kernel_events)]
+        k_avg = sum(k_ms) / len(k_ms)
+        r["attend_kernel_us"] = round(k_avg * 1e3, 2)
+        r["attend_kernel_GBps"] = round(sum(kb) / len(kb) / (k_avg * 1e-3) / 1e9, 1)
+        r["attend_kernel_frac_of_peak"] = round(r["attend_kernel_GBps"] / HBM_PEAK_GBS, 4)
+    return r
+
+
+def steady_cache(B, gen, wl, dev, n_layers=None, n0=None):
+    """A cache at steady state made by the input generator (not through the path): every layer holds
+    wl.steady_len slots, as right after a trigger (or n0 slots of a cache that has not triggered yet).
+    Returns (cache, t0) with t0 the decode step it stands for."""
+    import torch
+    L = wl.n_layers if n_layers is None else n_layers
+    cache = B.Cache.for_workload(wl, device=dev, n_layers=L)
+    t0 = wl.budget + wl.window + wl.evict_every   # the step of the first trigger: budget + window thinking tokens after it
+    if n0 is None:
+        n0 = wl.steady_len
+    else:
+        t0 = n0 - wl.prompt
+    for l in range(L):
+        st = gen.steady_state(l, n0)
+        if wl.external_scores:
+            ext = gen.external_scores(torch.arange(1, n0 - wl.prompt + 1))
+            st["S"][:, :, wl.prompt:] = ext.t().unsqueeze(1).expand(wl.batch, wl.n_kv_heads, n0 - wl.prompt)
+        cache.K[l, :, :, :n0] = st["K"]
+        cache.V[l, :, :, :n0] = st["V"]
+        cache.S[l, :, :, :n0] = st["S"]
+        cache.pos[l, :, :, :n0] = st["pos"]
+        del st
+    cache.seq_len.fill_(n0)
+    cache.next_pos.fill_(10 ** 6)
+    cache.n_prompt.fill_(wl.prompt)
+    return cache, t0
+
+
+def run_other_workloads(args, main_name):
+    """The other configurations of the benchmark, each at steady state for a few whole eviction periods: a bounded
+    companion to the main line (one period of warm-up, three timed, generator-made cache)."""
+    import dataclasses
+    import torch
+    from paper_2601_18383_amd import binding as B, configs, synth
+
+    dev = torch.device("cuda:0")
+    res = {}
+    for name in ("cfg1", "cfg2", "cfg3", "cfg4", "cfg5", "cfg5b", "cfg4_full_kv"):
+        if name == main_name:
+            continue
+        t_w = time.perf_counter()
+        note = None
+        n0 = None
+        if name == "cfg4_full_kv":
+            # the comparison without eviction at the END of cfg4's decode (steps 8129 .. 8192: every token still
+            # cached, 8640 -> 8704 slots), attention + append only, no scores; 4 of the 32 layers (9 GB of K/V)
+            base = configs.get("cfg4")
+            wl = dataclasses.replace(base, name=name, n_layers=4, budget=base.steps[1], window=0, evict_every=64,
+                                     external_scores=True)
+            n0 = base.prompt + base.steps[1] - 64
+            note = "cfg4 without eviction over decode steps 8145..8192 (8656..8704 cached slots), 4 of 32 layers, no trigger"
+        else:
+            wl = configs.get(name)
+        gen = synth.Synth(wl, dev)
+        cache, t0 = steady_cache(B, gen, wl, dev, n0=n0)
+        lengths = torch.full((wl.batch,), 10 ** 6, dtype=torch.int64)     # everybody active: steady state
+        out = torch.zeros((wl.n_layers, wl.batch, wl.n_q_heads, wl.head_dim), dtype=torch.float32, device=dev)
+        period = 16 if name == "cfg4_full_kv" else wl.evict_every
+        time_periods(B, cache, gen, wl, lengths, out, t0, dev, n_periods=1, period=period)                  # warm-up
+        r = time_periods(B, cache, gen, wl, lengths, out, t0 + period, dev, n_periods=3, kernel_events=256, period=period)
+        assert int(cache.status[0]) == 0, "device status word set in %s: %d" % (name, int(cache.status[0]))
+        r["layers"] = wl.n_layers
+        if note:
+            r["note"] = note
+        res[name] = r
+        cache.close()
+        del cache, out, gen
+        torch.cuda.empty_cache()
+        log("other workload %s: %s (%.1f s)" % (name, r, time.perf_counter() - t_w))
+    return res
+
+
 def run_gpu(args, wl):
     import torch
     from paper_2601_18383_amd import binding as B, synth
@@ -238,10 +359,18 @@ def run_gpu(args, wl):
         for ln in open(tf):
             if ln.startswith("hbm_bytes_per_launch:"):
                 traffic = int(ln.split(":")[1])
+    # ---- whole eviction periods (the "+evict" leg of the metric), when the requested window is too short to
+    # hold several: 5 in-stream windows of one period each, every one with exactly one trigger in it
+    full_period = None
+    if args.steps < 5 * E:
+        full_period = time_periods(B, cache, gen, wl, lengths, out, t_end + n_prof, dev, n_periods=5)
     stream = read_stream_rates(B, int(bytes_launch) // 16 * 16, dev)
     roofline = {"bound": "hbm", "kernel": "attend_kernel<%d,attend,pending,append>" % wl.head_dim,
                 "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
                 "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": traffic,
+                "traffic_source": ("profiles/attend_kernel_%s_hbm_counters.txt: rocprofv3 --pmc FETCH_SIZE and "
+                                   "WRITE_SIZE of this command, scaled by a 1 GiB copy; a committed summary, not "
+                                   "measured in this run" % wl.name) if traffic else None,
                 "kernel_avg_us": round(k_avg_ms * 1e3, 2), "algorithmic_bytes_per_launch": int(bytes_launch),
                 "launches_timed": len(k_ms), "plain_read_stream_GBps": stream,
                 "frac_of_plain_read_stream": round(achieved / max(stream.values()), 4)}
@@ -251,7 +380,7 @@ def run_gpu(args, wl):
     return dict(value=args.steps / dt, ms_per_step=dt / args.steps * 1e3, roofline=roofline,
                 whole_step_gbs=step_bytes / dt / 1e9, seq_steps_per_s=sum(act_counts) / dt,
                 evictions_timed=int(ft.sum()), first_timed_step=t + args.warmup + 1,
-                active_min=min(act_counts), active_max=max(act_counts),
+                active_min=min(act_counts), active_max=max(act_counts), full_period=full_period,
                 windows={"n": n_win, "steps_each": win, "ms_per_step_median": round(win_ms[len(win_ms) // 2], 5),
                          "ms_per_step_min": round(win_ms[0], 5), "ms_per_step_max": round(win_ms[-1], 5)})
 
@@ -481,7 +610,9 @@ def result_line(args, wl, r, cpu):
                                 r["active_min"], r["active_max"], wl.batch),
                    "first_timed_step": r["first_timed_step"], "evictions_in_window": r["evictions_timed"],
                    "sequence_steps_per_s": round(r["seq_steps_per_s"], 1), "timed_windows": r.get("windows"),
-                   "whole_step_algorithmic_GBps": round(r["whole_step_gbs"], 1)},
+                   "whole_step_algorithmic_GBps": round(r["whole_step_gbs"], 1),
+                   "full_period": r.get("full_period"), "other_workloads": r.get("other_workloads"),
+                   "memory_note": r.get("memory_note")},
         "roofline": r["roofline"], "cpu_baseline": cpu,
     }
     return line
@@ -496,6 +627,8 @@ def main():
     ap.add_argument("--layers", type=int, default=0, help="run only this many layers of the workload's stack "
                     "(a tuning aid; the workload line says so)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-other-workloads", action="store_true",
+                    help="skip the bounded runs of the other configurations that accompany the main line")
     ap.add_argument("--trajectory", action="store_true",
                     help="time the whole decode from the prompt to the end of the longest sequence (ragged "
                          "batches decay) instead of a steady-state window; --steps/--warmup are ignored")
@@ -545,6 +678,13 @@ def main():
         args.steps, args.warmup, args.no_cpu_baseline = r["steps"], 0, True
     else:
         r = run_gpu(args, wl)
+        kv_mb = 4.0 * wl.batch * wl.n_kv_heads * wl.steady_len * wl.head_dim / 1e6
+        r["memory_note"] = ("%.0f MB of K/V per layer-step, %d layer(s): %s" %
+                            (kv_mb, wl.n_layers, "re-read every step and below the 256 MB memory-side cache, which "
+                             "therefore serves part of it; cfg4 / cfg5 in other_workloads are the HBM-only cases"
+                             if kv_mb * wl.n_layers < 256 else "beyond the 256 MB memory-side cache: HBM only"))
+        if not args.no_other_workloads:
+            r["other_workloads"] = run_other_workloads(args, args.workload)
     if args.copy_calibration:
         import torch
         src = torch.ones(1 << 28, dtype=torch.float32, device="cuda:0")
