@@ -220,7 +220,8 @@ def steady_cache(B, gen, wl, dev, n_layers=None, n0=None):
 
 def run_other_workloads(args, main_name):
     """The other configurations of the benchmark, each at steady state for a few whole eviction periods: a bounded
-    companion to the main line (one period of warm-up, three timed, generator-made cache)."""
+    companion to the main line (cache brought to its third trigger through the path, one more period of warm-up,
+    three timed; all sequences are still decoding at that point)."""
     import dataclasses
     import torch
     from paper_2601_18383_amd import binding as B, configs, synth
@@ -244,9 +245,12 @@ def run_other_workloads(args, main_name):
         else:
             wl = configs.get(name)
         gen = synth.Synth(wl, dev)
-        cache, t0 = steady_cache(B, gen, wl, dev, n0=n0)
-        lengths = torch.full((wl.batch,), 10 ** 6, dtype=torch.int64)     # everybody active: steady state
-        out = torch.zeros((wl.n_layers, wl.batch, wl.n_q_heads, wl.head_dim), dtype=torch.float32, device=dev)
+        if name == "cfg4_full_kv":   # 8640 slots through the path would take minutes: the generator makes the state
+            cache, t0 = steady_cache(B, gen, wl, dev, n0=n0)
+            lengths = torch.full((wl.batch,), 10 ** 6, dtype=torch.int64)
+            out = torch.zeros((wl.n_layers, wl.batch, wl.n_q_heads, wl.head_dim), dtype=torch.float32, device=dev)
+        else:                        # through the path itself, so that the eviction pattern is the path's own
+            cache, out, lengths, t0 = run_up(B, gen, wl, dev)
         period = 16 if name == "cfg4_full_kv" else wl.evict_every
         time_periods(B, cache, gen, wl, lengths, out, t0, dev, n_periods=1, period=period)                  # warm-up
         r = time_periods(B, cache, gen, wl, lengths, out, t0 + period, dev, n_periods=3, kernel_events=256, period=period)
@@ -262,25 +266,19 @@ def run_other_workloads(args, main_name):
     return res
 
 
-def run_gpu(args, wl):
+def run_up(B, gen, wl, dev, paged=False, launch_shape=None, t_stop=None):
+    """A cache brought to steady state through the path itself (untimed): prompt rows, then decode steps up to
+    the third trigger (or t_stop).  Returns (cache, out, lengths, t) with t the last step taken."""
     import torch
-    from paper_2601_18383_amd import binding as B, synth
-
-    dev = torch.device("cuda:0")
-    props = torch.cuda.get_device_properties(0)
-    log("device: %s, %d CUs, %.0f GiB" % (props.name, props.multi_processor_count, props.total_memory / 2 ** 30))
-    gen = synth.Synth(wl, dev)
-    cache = (B.PagedCache if args.paged else B.Cache).for_workload(wl, device=dev, launch_shape=args.launch_shape)
+    cache = (B.PagedCache if paged else B.Cache).for_workload(wl, device=dev, launch_shape=launch_shape)
     L = wl.n_layers
     for l in range(L):
         K0, V0 = gen.prompt_kv(l)
         m = torch.full((wl.batch,), wl.prompt, dtype=torch.int32, device=dev)
         B.dynts_prefill(cache.ctx, l, K0, V0, m)
     out = torch.zeros((L, wl.batch, wl.n_q_heads, wl.head_dim), dtype=torch.float32, device=dev)
-
-    # ---- bring the cache to steady state through the path itself (untimed) -----------------
     E = wl.evict_every
-    t_steady = (wl.budget + wl.window + E) + 2 * E       # the step of the third trigger
+    t_steady = (wl.budget + wl.window + E) + 2 * E if t_stop is None else t_stop   # the step of the third trigger
     lengths = gen.decode_lengths()  # per-sequence decode lengths (ragged workloads); finished ones are masked
     per_step = L * wl.batch * (wl.n_q_heads + 2 * wl.n_kv_heads) * wl.head_dim * 2
     block = max(1, min(256, (1 << 30) // per_step))   # input pool of at most 1 GiB
@@ -294,8 +292,21 @@ def run_gpu(args, wl):
                             evict_steps=evict_flags(wl, t, n), trigger=act)
         t += n
     torch.cuda.synchronize()
-    log("steady state reached at step %d in %.1f s; seq_len[0,0]=%d status=%d" %
-        (t, time.perf_counter() - t_pre, int(cache.seq_len[0, 0]), int(cache.status[0])))
+    log("%s: steady state reached at step %d in %.1f s; seq_len[0,0]=%d status=%d" %
+        (wl.name, t, time.perf_counter() - t_pre, int(cache.seq_len[0, 0]), int(cache.status[0])))
+    return cache, out, lengths, t
+
+
+def run_gpu(args, wl):
+    import torch
+    from paper_2601_18383_amd import binding as B, synth
+
+    dev = torch.device("cuda:0")
+    props = torch.cuda.get_device_properties(0)
+    log("device: %s, %d CUs, %.0f GiB" % (props.name, props.multi_processor_count, props.total_memory / 2 ** 30))
+    gen = synth.Synth(wl, dev)
+    cache, out, lengths, t = run_up(B, gen, wl, dev, paged=args.paged, launch_shape=args.launch_shape)
+    L, E = wl.n_layers, wl.evict_every
 
     # ---- warmup + timed window, inputs resident ---------------------------------------------
     qw, kw, vw, sw = make_pools(gen, wl, t, args.warmup, dev) if args.warmup else (None,) * 4
@@ -332,7 +343,7 @@ def run_gpu(args, wl):
     assert int(cache.seq_len[0, longest]) == cache_len_before_step(wl, t_end + 1) - 1
 
     # ---- the streaming kernel alone, timed with HIP events recorded by the library ------------
-    n_prof = min(args.steps, 64) // E * E or min(args.steps, 64)
+    n_prof = 64 // E * E or 64   # a pass of its own, whatever --steps says: whole periods, 64 steps
     qp, kp, vp, sp = make_pools(gen, wl, t_end, n_prof, dev)
     fp = evict_flags(wl, t_end, n_prof)
     # (the same native loop as the timed window, so the launches are back to back; every attend launch
