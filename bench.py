@@ -482,6 +482,17 @@ def run_score_block(args, wl):
     torch.cuda.synchronize()
     dt = time.perf_counter() - t0
     ev_ms = e0.elapsed_time(e1) / args.steps
+    # the second roofline: exponentials.  Rate of the vector ALUs measured by the library's probe (2048 workgroups
+    # of 256 lanes, 4000 x 8 exponentials + subtractions per lane), in the same process
+    sink = torch.zeros(4, dtype=torch.float32, device=dev)
+    hev = HipEvents(1)
+    rates = []
+    for _ in range(4):
+        B.dynts_probe_exp_rate(2048, 4000, sink, hev.pairs[0][0], hev.pairs[0][1])
+        torch.cuda.synchronize()
+        rates.append(2048 * 256 * 4000 * 8 / (hev.elapsed_ms(0) * 1e-3))
+    hev.close()
+    exp_rate = max(rates[1:])
     units, R, d = wl.batch * wl.n_kv_heads, T * wl.group, wl.head_dim
     # the contraction the method defines: every query row against the cached slots and its visible block keys
     flops = units * 2.0 * d * (R * n0 + wl.group * T * (T + 1) / 2)
@@ -491,7 +502,13 @@ def run_score_block(args, wl):
                 "achieved": round(flops / (ev_ms * 1e-3) / 1e12, 1), "peak": peak, "unit": "TFLOP/s",
                 "frac": round(flops / (ev_ms * 1e-3) / 1e12 / peak, 4), "traffic": None,
                 "call_avg_us": round(ev_ms * 1e3, 1), "algorithmic_flops_per_call": flops,
-                "executed_mfma_flops_per_call": executed, "exp2_per_call": units * (2.0 * R * n0)}
+                "executed_mfma_flops_per_call": executed, "exp2_per_call": units * (2.0 * R * n0),
+                "second_bound": {"kind": "v_exp_f32 issue (one exponential and one subtraction per (query row, slot) "
+                                         "and pass, two passes)",
+                                 "peak_exp2_per_s": round(exp_rate / 1e12, 2), "unit": "T/s, measured by "
+                                 "dynts_probe_exp_rate in this run",
+                                 "achieved_exp2_per_s": round(units * (2.0 * R * n0) / (ev_ms * 1e-3) / 1e12, 2),
+                                 "frac": round(units * (2.0 * R * n0) / (ev_ms * 1e-3) / exp_rate, 4)}}
     return dict(value=args.steps / dt, ms_per_step=dt / args.steps * 1e3, roofline=roofline,
                 whole_step_gbs=0.0, seq_steps_per_s=args.steps * wl.batch / dt, evictions_timed=0,
                 first_timed_step=0, active_min=wl.batch, active_max=wl.batch)

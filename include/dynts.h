@@ -293,6 +293,13 @@ int dynts_predict_scores(const dynts_predictor *w, const uint16_t *h, int32_t ba
 int dynts_probe_read_stream(const void *buf, size_t bytes, int32_t n_workgroups, uint32_t magic,
                             uint32_t *sink, void *start, void *stop, void *stream);
 
+/* Measurement aid, not part of the method: one launch in which every lane of n_workgroups x 256 lanes performs
+ * iters x 8 exponentials 2^x followed by a subtraction (the loop holds nothing else), 16 * iters instructions per
+ * wave.  The exponentials delivered per second are the second roofline of dynts_score_block, which needs one
+ * per (query row, slot) and pass (Eq. attn-score's softmax).  sink: one device float, written only on a value
+ * that cannot occur.  start/stop: hipEvent_t handles attached to the dispatch, or both NULL. */
+int dynts_probe_exp_rate(int32_t n_workgroups, int32_t iters, float *sink, void *start, void *stop, void *stream);
+
 #ifdef __cplusplus
 }
 #endif

@@ -764,6 +764,16 @@ int dynts_probe_read_stream(const void *buf, size_t bytes, int32_t n_workgroups,
   return launch_status();
 }
 
+int dynts_probe_exp_rate(int32_t n_workgroups, int32_t iters, float *sink, void *start, void *stop, void *stream) {
+  if (!sink) return DYNTS_ENULL;
+  if (n_workgroups <= 0 || n_workgroups > (1 << 20) || iters <= 0) return DYNTS_EINVAL;
+  if ((start == nullptr) != (stop == nullptr)) return DYNTS_EINVAL;
+  hipExtLaunchKernelGGL(dynts::exp2_rate_kernel, dim3(n_workgroups), dim3(dynts::kProbeThreads), 0,
+                        static_cast<hipStream_t>(stream), static_cast<hipEvent_t>(start),
+                        static_cast<hipEvent_t>(stop), 0, iters, -12345.678f, sink);
+  return launch_status();
+}
+
 int dynts_decode_loop(dynts_ctx *ctx, int32_t n_steps, const uint16_t *q, const uint16_t *k_new,
                       const uint16_t *v_new, const float *s_new, const uint8_t *active, const uint8_t *evict_steps,
                       const uint8_t *trigger, float *out, size_t out_step_stride, int32_t *keep_idx,

@@ -32,4 +32,22 @@ __global__ __launch_bounds__(kProbeThreads) void read_stream_kernel(const uint32
   if (x == magic) sink[0] = x;
 }
 
+// Second measurement aid: how many 2^x the vector ALUs deliver.  Every lane runs `iters` rounds of eight
+// independent v_exp_f32 (arguments stay in (0, 1], nothing else in the loop); nothing is written unless the sum
+// equals `magic`.  The block-scoring kernels need one exponential per (query row, slot) and pass, which is what
+// bounds them besides the matrix cores.
+__global__ __launch_bounds__(kProbeThreads) void exp2_rate_kernel(int iters, float magic, float *sink) {
+  float a[8];
+#pragma unroll
+  for (int i = 0; i < 8; ++i) a[i] = 1.0f / (float)(1 + ((threadIdx.x + i) & 15));
+  for (int it = 0; it < iters; ++it) {
+#pragma unroll
+    for (int i = 0; i < 8; ++i) a[i] = __builtin_amdgcn_exp2f(a[i]) - 1.0f;  // 2^a - 1 stays in (0, 1]
+  }
+  float s = 0.f;
+#pragma unroll
+  for (int i = 0; i < 8; ++i) s += a[i];
+  if (s == magic) sink[0] = s;
+}
+
 }  // namespace dynts

@@ -86,7 +86,10 @@ struct SbStage {
   static constexpr int PIECES = D / 8;           // 16-byte pieces per row
   static constexpr int RPP = 256 / PIECES;       // rows one load instruction of the workgroup covers
   static constexpr int NL = kChunk / RPP;        // load instructions per chunk and thread
-  static constexpr int LROW = 2 * D + 16;        // padded row pitch in LDS, bytes
+#ifndef SB_PITCH_EXTRA
+#define SB_PITCH_EXTRA 16
+#endif
+  static constexpr int LROW = 2 * D + SB_PITCH_EXTRA;        // padded row pitch in LDS, bytes
   static constexpr int kBufBytes = kChunk * LROW;
 };
 
