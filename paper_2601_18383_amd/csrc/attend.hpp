@@ -162,7 +162,8 @@ __device__ __forceinline__ void wave_lds_fence() {
   __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
 }
 
-template <int D, int W, bool ATTEND, bool PENDING, bool APPEND, bool PAGED = false>
+// BURST: updated scores leave in bursts through LDS (see flush_scores) instead of tile by tile.
+template <int D, int W, bool ATTEND, bool PENDING, bool APPEND, bool PAGED = false, bool BURST = false>
 __global__ __launch_bounds__(W * 64, 2) void attend_kernel(const AttendParams p) {
   constexpr int kWaves = W, kThreads = W * 64;
   constexpr int KS = D / 32;              // MFMA k-steps per K row
@@ -181,13 +182,21 @@ __global__ __launch_bounds__(W * 64, 2) void attend_kernel(const AttendParams p)
   __shared__ int32_t sm_hdr[5];
   // updated scores of up to kScoreTiles consecutive tiles per wave, written out together (see flush_scores)
   constexpr int kScoreTiles = 16;
-  __shared__ __align__(16) float sm_score[PENDING ? kWaves : 1][PENDING ? kScoreTiles * kTile : 4];
+  __shared__ __align__(16) float sm_score[PENDING && BURST ? kWaves : 1][PENDING && BURST ? kScoreTiles * kTile : 4];
 
   const int tid = threadIdx.x;
   const int lane = tid & 63, wave = tid >> 6;
   const int r16 = lane & 15, kg = lane >> 4;
   const int g = r16;  // query head (within the group) of this lane's logits
-  const int split = blockIdx.x, h = blockIdx.y, b = blockIdx.z;
+  // Workgroup -> (unit, chunk).  Consecutive workgroup ids go to the 8 XCDs in turn; the chunks of one
+  // (sequence, KV head) unit get ids that are 8 apart, so that they normally run on ONE XCD and their
+  // hand-off of partials travels through that XCD's L2 (measured: a round trip between workgroups costs
+  // about 0.55 us inside an XCD, 0.7 - 0.9 us across).  Nothing depends on the placement but speed.
+  // grid = round_up(units, 8) * nsplit; the padding workgroups leave at once.
+  const int wg = blockIdx.x, per_grp = 8 * p.nsplit;
+  const int split = (wg % per_grp) >> 3, u_lin = (wg / per_grp) * 8 + (wg & 7);
+  if (u_lin >= p.Nb * p.Hkv) return;
+  const int b = u_lin / p.Hkv, h = u_lin - b * p.Hkv;
   const int G = p.G;
 
   const size_t unit = (size_t)b * p.Hkv + h;
@@ -480,10 +489,10 @@ __global__ __launch_bounds__(W * 64, 2) void attend_kernel(const AttendParams p)
   // 16 bytes per lane at once: when the run breaks, when score_tiles have gathered, and when the wave is
   // done.  sc_base: first slot of the run, sc_n: tiles in it, [sc_lo, sc_hi): the slots that may be written
   // (thinking slots below the end of the deferred update and of this wave's share).
-  float *sbuf = sm_score[PENDING ? wave : 0];
+  float *sbuf = sm_score[PENDING && BURST ? wave : 0];
   int sc_base = 0, sc_n = 0, sc_lo = 0, sc_hi = 0;
   auto flush_scores = [&]() {
-    if (!PENDING || sc_n == 0) return;
+    if (!PENDING || !BURST || sc_n == 0) return;
     wave_lds_fence();
     for (int c0 = 0; c0 < sc_n * kTile; c0 += 256) {
       const int off = c0 + 4 * lane;
@@ -562,7 +571,7 @@ __global__ __launch_bounds__(W * 64, 2) void attend_kernel(const AttendParams p)
       }
       // lane < 32 holds the new score of slot t + lane (sub-tile kg, row r16): write it, or park it
       const float s_upd = s_cur + (kg == 0 ? part[0] : part[1]);
-      if (p.score_tiles <= 1) {
+      if (!BURST) {
         const int tok = t + lane;
         if (lane < kTile && tok < pend_hi && tok >= M) Sb[tok] = s_upd;
       } else {

@@ -162,12 +162,18 @@ LayerView layer_view(const dynts_ctx *ctx, int layer) {
 // kernel's own begin and end
 template <int D, int W, bool ATTEND, bool PENDING, bool APPEND>
 void launch_partial(const dynts::AttendParams &p, dim3 grid, hipStream_t st, hipEvent_t start, hipEvent_t stop) {
-  if (p.block_table)
-    hipExtLaunchKernelGGL((dynts::attend_kernel<D, W, ATTEND, PENDING, APPEND, true>), grid, dim3(W * 64), 0, st, start,
-                          stop, 0, p);
-  else
-    hipExtLaunchKernelGGL((dynts::attend_kernel<D, W, ATTEND, PENDING, APPEND, false>), grid, dim3(W * 64), 0, st, start,
-                          stop, 0, p);
+  const bool burst = PENDING && p.score_tiles > 1;  // score writes in bursts: a kernel variant of its own (registers)
+#define DYNTS_LAUNCH(PAGED, BURST)                                                                                  \
+  hipExtLaunchKernelGGL((dynts::attend_kernel<D, W, ATTEND, PENDING, APPEND, PAGED, BURST>), grid, dim3(W * 64), 0, \
+                        st, start, stop, 0, p)
+  if (p.block_table) {
+    if (burst) DYNTS_LAUNCH(true, PENDING);
+    else DYNTS_LAUNCH(true, false);
+  } else {
+    if (burst) DYNTS_LAUNCH(false, PENDING);
+    else DYNTS_LAUNCH(false, false);
+  }
+#undef DYNTS_LAUNCH
 }
 
 template <int D, int W>
@@ -228,7 +234,10 @@ int run_attend(dynts_ctx *ctx, int layer, const uint16_t *q, const uint16_t *k_n
   p.block_table = lv.block_table; p.block_table_w = lv.block_table; p.free_stack = ctx->free_stack;
   p.free_top = ctx->free_top; p.max_pages = ctx->max_pages; p.n_pages = ctx->n_pages;
 
-  const dim3 grid(pl.nsplit, c.n_kv_heads, c.batch);
+  // one-dimensional grid: units rounded up to the 8 XCDs, times the chunks per unit (mapped inside the kernel)
+  const long long units8 = ((long long)c.batch * c.n_kv_heads + 7) / 8 * 8;
+  if (units8 * pl.nsplit > 0x7fffffffLL) return DYNTS_ESHAPE;
+  const dim3 grid((unsigned)(units8 * pl.nsplit));
   hipEvent_t e0 = ctx->ev_start, e1 = ctx->ev_stop;
   if (attend && ctx->ev_list_next < ctx->ev_list_start.size()) {
     e0 = ctx->ev_list_start[ctx->ev_list_next];
