@@ -799,9 +799,6 @@ __global__ __launch_bounds__(W * 64, 2) void attend_kernel(const AttendParams p)
     L_e[k] = 0.f;
     o_e[k] = 0.f;
   }
-#ifdef EXP_MERGER_WAITS
-  asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-#endif
   for (int s0 = 0; s0 < chunks_now; s0 += kMergeGroup) {
     ask_group(s0);
     while (!group_fresh()) ask_group(s0);  // a word that is not this launch's yet is on its way: ask again
