@@ -365,7 +365,7 @@ def run_gpu(args, wl):
     bytes_launch = sum(launch_bytes) / len(launch_bytes)
     achieved = bytes_launch / (k_avg_ms * 1e-3) / 1e9
     traffic = None  # HBM bytes per launch from the committed rocprofv3 counter summary, if there is one
-    tf = os.path.join(ROOT, "profiles", "attend_kernel_%s_hbm_counters.txt" % wl.name)
+    tf = os.path.join(ROOT, "profiles", "attend_kernel_%s_hbm_counters.txt" % args.workload)
     if os.path.exists(tf):
         for ln in open(tf):
             if ln.startswith("hbm_bytes_per_launch:"):
@@ -380,8 +380,8 @@ def run_gpu(args, wl):
                 "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
                 "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": traffic,
                 "traffic_source": ("profiles/attend_kernel_%s_hbm_counters.txt: rocprofv3 --pmc FETCH_SIZE and "
-                                   "WRITE_SIZE of this command, scaled by a 1 GiB copy; a committed summary, not "
-                                   "measured in this run" % wl.name) if traffic else None,
+                                   "WRITE_SIZE of this workload's steady state, scaled by a 1 GiB copy; a committed "
+                                   "summary, not measured in this run" % args.workload) if traffic else None,
                 "kernel_avg_us": round(k_avg_ms * 1e3, 2), "algorithmic_bytes_per_launch": int(bytes_launch),
                 "launches_timed": len(k_ms), "plain_read_stream_GBps": stream,
                 "frac_of_plain_read_stream": round(achieved / max(stream.values()), 4)}
