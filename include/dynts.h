@@ -181,6 +181,14 @@ int dynts_decode_step_static(dynts_ctx *ctx, int32_t layer, const uint16_t *q, c
                              const uint16_t *v_new, const float *s_new, const uint8_t *active,
                              float *out, float *lse, void *stream);
 
+/* Optional announcement: the next fused step of this layer (dynts_decode_step, dynts_decode_step_static or
+ * dynts_decode_attend_update) will be followed by a trigger (dynts_select_evict).  That step then keeps its
+ * logits (4 bytes per slot and query head of the group, in the workspace), and the score accumulation it owes
+ * is applied from them when dynts_select_evict / dynts_update_scores asks for it, instead of by a second pass
+ * over K.  Results are the same up to fp32 rounding order; without the announcement everything works as before.
+ * dynts_decode_loop makes it itself on the steps flagged in evict_steps.  No effect with external scores. */
+int dynts_hint_trigger(dynts_ctx *ctx, int32_t layer);
+
 /* KV-cache selection (Sec. 4.2, third paragraph): for every sequence with trigger[b] != 0
  * (uint8 [Nb], NULL = all) and every KV head keep all question slots, the last `window`
  * slots, and of the slots between them the k_keep with the highest score (ties: lower

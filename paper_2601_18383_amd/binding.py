@@ -25,7 +25,7 @@ EXPORTS = [
     "dynts_score_block_scratch_bytes", "dynts_score_block",
     "dynts_predict_scratch_bytes", "dynts_predict_scores", "dynts_predictor_pack", "dynts_bind_paged",
     "dynts_set_launch_shape", "dynts_ctx_workspace_bytes",
-    "dynts_decode_step_static", "dynts_probe_exp_rate",
+    "dynts_decode_step_static", "dynts_probe_exp_rate", "dynts_hint_trigger",
 ]
 
 
@@ -71,6 +71,7 @@ def _load():
     lib.dynts_decode_attend_update.argtypes = [vp, i32, vp, vp, vp, vp, vp]
     lib.dynts_decode_step.argtypes = [vp, i32, vp, vp, vp, vp, vp, vp, vp, vp]
     lib.dynts_decode_step_static.argtypes = [vp, i32, vp, vp, vp, vp, vp, vp, vp, vp]
+    lib.dynts_hint_trigger.argtypes = [vp, i32]
     lib.dynts_select_evict.argtypes = [vp, i32, vp, i32, vp, i32, vp, vp]
     lib.dynts_compact.argtypes = [vp, i32, vp, vp, i32, vp, vp]
     lib.dynts_decode_loop.argtypes = [vp, i32, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp, vp, vp]
@@ -218,6 +219,10 @@ def dynts_decode_step_static(ctx, layer, q, k_new, v_new, out, s_new=None, activ
 
 
 DYNTS_STATIC_SCRATCH_BYTES = 8 << 20
+
+
+def dynts_hint_trigger(ctx, layer):
+    _check(lib.dynts_hint_trigger(ctx, layer), "dynts_hint_trigger")
 
 
 def dynts_select_evict(ctx, layer, keep_idx, new_len, k_keep=-1, trigger=None, stream=None):

@@ -64,6 +64,11 @@ struct AttendParams {
   uint64_t *part_ml;        // [Nb][Hkv][nsplit][G][2]
   uint32_t tag;             // this launch's serial number (never 0)
   int score_tiles;          // updated scores are written out every so many tiles of a wave (1 .. 16)
+  // When a trigger is known to follow this step, the step's own scaled logits (log2 units) are kept,
+  // [Nb][Hkv][G][cap_pad] fp32, so that its score update can be applied from them (apply_spill_kernel) instead of
+  // a second pass over K.  Null: not kept.
+  float *spill;
+  int cap_pad;              // cap rounded up to a whole tile: row pitch of the kept logits (a tile's store stays inside its row)
   uint32_t *unit_cnt;       // [Nb][Hkv] ticket counters, zero between launches
   uint32_t *seq_cnt;        // [Nb]      arrival counters, zero between launches
   int32_t *status;
@@ -163,7 +168,8 @@ __device__ __forceinline__ void wave_lds_fence() {
 }
 
 // BURST: updated scores leave in bursts through LDS (see flush_scores) instead of tile by tile.
-template <int D, int W, bool ATTEND, bool PENDING, bool APPEND, bool PAGED = false, bool BURST = false>
+// SPILL: the step keeps its logits (AttendParams::spill) for a trigger that follows.
+template <int D, int W, bool ATTEND, bool PENDING, bool APPEND, bool PAGED = false, bool BURST = false, bool SPILL = false>
 __global__ __launch_bounds__(W * 64, 2) void attend_kernel(const AttendParams p) {
   constexpr int kWaves = W, kThreads = W * 64;
   constexpr int KS = D / 32;              // MFMA k-steps per K row
@@ -417,6 +423,7 @@ __global__ __launch_bounds__(W * 64, 2) void attend_kernel(const AttendParams p)
     for (int ks = 0; ks < KS; ++ks) a0 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kn[ks], qf[ks], a0, 0, 0, 0);
     m_run = a0[0] * p.scale_log2;
     l_run = kg == 0 ? 1.f : 0.f;  // per-lane partial sums are added over kg at the end
+    if (SPILL && kg == 0 && g < G) p.spill[(unit * G + g) * (size_t)p.cap_pad + n_old] = m_run;
 #pragma unroll
     for (int cb = 0; cb < CB; ++cb) {
       typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
@@ -603,6 +610,21 @@ __global__ __launch_bounds__(W * 64, 2) void attend_kernel(const AttendParams p)
           const int tok = t + 16 * (e >> 2) + 4 * kg + (e & 3);
           x[e] = tok < att_hi ? acc[e >> 2][e & 3] * p.scale_log2 : -INFINITY;
           mx = fmaxf(mx, x[e]);
+        }
+      }
+      if (SPILL && g < G) {  // this lane's 8 logits of head g: slots t + 16 s + 4 kg .. +3
+        // (only slots this tile attends: the slot behind them may be the appended token's, kept by its own wave)
+        float *sp = p.spill + (unit * G + g) * (size_t)p.cap_pad + t + 4 * kg;
+#pragma unroll
+        for (int s2 = 0; s2 < 2; ++s2) {
+          const int s_lo = t + 16 * s2 + 4 * kg;
+          if (s_lo + 4 <= att_hi) {
+            *reinterpret_cast<f32x4 *>(sp + 16 * s2) = f32x4{x[4 * s2], x[4 * s2 + 1], x[4 * s2 + 2], x[4 * s2 + 3]};
+          } else {
+#pragma unroll
+            for (int i = 0; i < 4; ++i)
+              if (s_lo + i < att_hi) sp[16 * s2 + i] = x[4 * s2 + i];
+          }
         }
       }
       mx = fmaxf(mx, __shfl_xor(mx, 16));
@@ -847,6 +869,34 @@ __global__ __launch_bounds__(W * 64, 2) void attend_kernel(const AttendParams p)
       }
     }
   }
+}
+
+// The score update of a step whose logits were kept (AttendParams::spill): S[slot] += sum over the group of
+// 2^(logit - max) / sum, for the thinking slots that step attended, with that step's final softmax
+// statistics -- the same arithmetic as the deferred update inside attend_kernel, fed from 4 * G bytes per slot
+// instead of a K row.  grid (ceil(cap / (256 * kApplyPerThread)), Hkv * Nb), 256 threads.
+constexpr int kApplyPerThread = 4;
+__global__ __launch_bounds__(256) void apply_spill_kernel(float *S, const float *spill, const float *mlprev,
+                                                          const int32_t *nprev, const int32_t *n_prompt, int Hkv, int Hq,
+                                                          int G, int cap, int cap_pad) {
+  const int unit = blockIdx.y, b = unit / Hkv, h = unit - b * Hkv;
+  const int n = nprev[b] < cap ? nprev[b] : cap, M = n_prompt[b];
+  const int j0 = (blockIdx.x * 256 + threadIdx.x) * kApplyPerThread;
+  if (j0 >= n || j0 + kApplyPerThread <= M) return;
+  float add[kApplyPerThread];
+#pragma unroll
+  for (int i = 0; i < kApplyPerThread; ++i) add[i] = 0.f;
+  for (int g = 0; g < G; ++g) {
+    const float *ml = mlprev + ((size_t)b * Hq + (size_t)h * G + g) * 2;
+    const float m = ml[0], inv_l = 1.0f / ml[1];
+    const f32x4 x = *reinterpret_cast<const f32x4 *>(spill + ((size_t)unit * G + g) * cap_pad + j0);
+#pragma unroll
+    for (int i = 0; i < kApplyPerThread; ++i) add[i] += fast_exp2(x[i] - m) * inv_l;
+  }
+  float *Su = S + (size_t)unit * cap;
+#pragma unroll
+  for (int i = 0; i < kApplyPerThread; ++i)
+    if (j0 + i < n && j0 + i >= M) Su[j0 + i] += add[i];
 }
 
 }  // namespace dynts

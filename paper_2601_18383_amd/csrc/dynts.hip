@@ -30,7 +30,8 @@ size_t align_up(size_t v) { return (v + kAlign - 1) / kAlign * kAlign; }
 
 struct Plan {
   int G = 0, waves = 0, chunk = 0, nsplit = 0;
-  size_t off_part_o = 0, off_part_ml = 0, off_unit_cnt = 0, off_seq_cnt = 0, off_qprev = 0, off_mlprev = 0, off_nprev = 0;
+  size_t off_part_o = 0, off_part_ml = 0, off_unit_cnt = 0, off_seq_cnt = 0, off_qprev = 0, off_mlprev = 0, off_nprev = 0, off_spill = 0;
+  int cap_pad = 0;
   size_t bytes = 0;
 };
 
@@ -79,6 +80,10 @@ Plan make_plan(const dynts_config &c, int target_wgs, int waves) {
   p.off_qprev = off;   off = align_up(off + 2 * LB * c.n_q_heads * c.head_dim * sizeof(uint16_t));  // two copies, used in turn
   p.off_mlprev = off;  off = align_up(off + LB * c.n_q_heads * 2 * sizeof(float));
   p.off_nprev = off;   off = align_up(off + LB * sizeof(int32_t));
+  // the logits of one step of one layer, kept when a trigger is known to follow (score_mode accumulate only)
+  p.cap_pad = (c.capacity + dynts::kTile - 1) / dynts::kTile * dynts::kTile;
+  p.off_spill = off;
+  if (c.score_mode == DYNTS_SCORE_ACCUMULATE) off = align_up(off + (size_t)units * p.G * p.cap_pad * sizeof(float));
   p.bytes = off;
   return p;
 }
@@ -94,7 +99,9 @@ struct dynts_ctx {
   float *S = nullptr;
   int32_t *pos = nullptr, *seq_len = nullptr, *next_pos = nullptr, *n_prompt = nullptr, *status = nullptr;
   unsigned char *ws = nullptr;
-  std::vector<unsigned char> pending;  // per layer: a score update is owed
+  std::vector<unsigned char> pending;  // per layer: a score update is owed (1: by a pass over K, 2: from kept logits)
+  std::vector<unsigned char> hint;     // per layer: a trigger follows the next fused step, keep its logits
+  int spill_layer = -1;                // the layer whose kept logits are waiting to be applied, or -1
   std::vector<unsigned char> qslot;    // per layer: which copy of the saved query is current
   hipEvent_t ev_start = nullptr, ev_stop = nullptr;
   std::vector<hipEvent_t> ev_list_start, ev_list_stop;  // one pair per coming attend launch
@@ -163,16 +170,21 @@ LayerView layer_view(const dynts_ctx *ctx, int layer) {
 template <int D, int W, bool ATTEND, bool PENDING, bool APPEND>
 void launch_partial(const dynts::AttendParams &p, dim3 grid, hipStream_t st, hipEvent_t start, hipEvent_t stop) {
   const bool burst = PENDING && p.score_tiles > 1;  // score writes in bursts: a kernel variant of its own (registers)
-#define DYNTS_LAUNCH(PAGED, BURST)                                                                                  \
-  hipExtLaunchKernelGGL((dynts::attend_kernel<D, W, ATTEND, PENDING, APPEND, PAGED, BURST>), grid, dim3(W * 64), 0, \
-                        st, start, stop, 0, p)
+  const bool spill = ATTEND && p.spill != nullptr;   // so is the step that keeps its logits
+#define DYNTS_LAUNCH(PAGED, BURST, SPILL)                                                                           \
+  hipExtLaunchKernelGGL((dynts::attend_kernel<D, W, ATTEND, PENDING, APPEND, PAGED, BURST, SPILL>), grid,            \
+                        dim3(W * 64), 0, st, start, stop, 0, p)
+#define DYNTS_LAUNCH2(PAGED, BURST)              \
+  if (spill) DYNTS_LAUNCH(PAGED, BURST, ATTEND); \
+  else DYNTS_LAUNCH(PAGED, BURST, false)
   if (p.block_table) {
-    if (burst) DYNTS_LAUNCH(true, PENDING);
-    else DYNTS_LAUNCH(true, false);
+    if (burst) { DYNTS_LAUNCH2(true, PENDING); }
+    else { DYNTS_LAUNCH2(true, false); }
   } else {
-    if (burst) DYNTS_LAUNCH(false, PENDING);
-    else DYNTS_LAUNCH(false, false);
+    if (burst) { DYNTS_LAUNCH2(false, PENDING); }
+    else { DYNTS_LAUNCH2(false, false); }
   }
+#undef DYNTS_LAUNCH2
 #undef DYNTS_LAUNCH
 }
 
@@ -197,7 +209,8 @@ struct Transient {
 // attend (optionally with fused append) and/or the deferred score update of one layer
 int run_attend(dynts_ctx *ctx, int layer, const uint16_t *q, const uint16_t *k_new, const uint16_t *v_new,
                const float *s_new, const uint8_t *active, float *out, float *lse, bool attend,
-               bool apply_pending, bool append, hipStream_t st, const Transient *transient = nullptr) {
+               bool apply_pending, bool append, hipStream_t st, const Transient *transient = nullptr,
+               bool keep_logits = false) {
   // transient: where the split partials and the counters of this launch live (default: the head of the
   // workspace); what must survive from one step to the next is always in the workspace
   const dynts_config &c = ctx->cfg;
@@ -226,6 +239,8 @@ int run_attend(dynts_ctx *ctx, int layer, const uint16_t *q, const uint16_t *k_n
   // score writes: tile by tile while the layer's K and V fit the memory-side cache (256 MB), in bursts beyond
   const double kv_bytes = 4.0 * c.batch * c.n_kv_heads * (double)c.capacity * c.head_dim;
   p.score_tiles = kv_bytes > 192e6 ? 16 : 1;
+  p.spill = keep_logits ? reinterpret_cast<float *>(ctx->ws + pl.off_spill) : nullptr;
+  p.cap_pad = pl.cap_pad;
   p.unit_cnt = tr.unit_cnt;
   p.seq_cnt = tr.seq_cnt;
   p.status = ctx->status;
@@ -256,6 +271,45 @@ int run_attend(dynts_ctx *ctx, int layer, const uint16_t *q, const uint16_t *k_n
   return rc;
 }
 
+
+// the score update of `layer` from its kept logits (pending == 2)
+int apply_spill(dynts_ctx *ctx, int layer, hipStream_t st) {
+  const dynts_config &c = ctx->cfg;
+  const Plan &pl = ctx->plan;
+  const LayerView lv = layer_view(ctx, layer);
+  const dim3 grid((c.capacity + 256 * dynts::kApplyPerThread - 1) / (256 * dynts::kApplyPerThread), c.n_kv_heads * c.batch);
+  hipLaunchKernelGGL(dynts::apply_spill_kernel, grid, dim3(256), 0, st, lv.S,
+                     reinterpret_cast<const float *>(ctx->ws + pl.off_spill), lv.mlprev, lv.nprev, ctx->n_prompt,
+                     c.n_kv_heads, c.n_q_heads, pl.G, c.capacity, pl.cap_pad);
+  const int rc = launch_status();
+  if (rc == DYNTS_OK) {
+    ctx->pending[layer] = 0;
+    ctx->spill_layer = -1;
+  }
+  return rc;
+}
+
+// One fused step (attention, the score update owed by the previous step, optionally the append) with the
+// bookkeeping of owed updates.  With a trigger announced for this layer (dynts_hint_trigger) the step keeps its
+// logits, and its own update is later applied from them instead of from a second pass over K.
+int fused_step(dynts_ctx *ctx, int layer, const uint16_t *q, const uint16_t *k_new, const uint16_t *v_new,
+               const float *s_new, const uint8_t *active, float *out, float *lse, bool append, hipStream_t st,
+               const Transient *transient) {
+  const bool track = ctx->cfg.score_mode == DYNTS_SCORE_ACCUMULATE;
+  const bool keep = track && ctx->hint[layer];
+  ctx->hint[layer] = 0;
+  int rc = DYNTS_OK;
+  if (ctx->pending[layer] == 2) rc = apply_spill(ctx, layer, st);
+  if (rc == DYNTS_OK && keep && ctx->spill_layer >= 0) rc = apply_spill(ctx, ctx->spill_layer, st);  // the buffer is reused
+  if (rc != DYNTS_OK) return rc;
+  rc = run_attend(ctx, layer, q, k_new, v_new, s_new, active, out, lse, true, ctx->pending[layer] == 1, append, st,
+                  transient, keep);
+  if (rc == DYNTS_OK) {
+    ctx->pending[layer] = track ? (keep ? 2 : 1) : 0;
+    if (keep) ctx->spill_layer = layer;
+  }
+  return rc;
+}
 
 // ---- Importance Predictor ---------------------------------------------------------------------------
 struct MlpPlan {
@@ -382,6 +436,7 @@ int dynts_create(const dynts_config *cfg, dynts_ctx **out) {
   const float scale = cfg->softmax_scale > 0.f ? cfg->softmax_scale : 1.0f / std::sqrt((float)cfg->head_dim);
   ctx->scale_log2 = scale * 1.4426950408889634f;
   ctx->pending.assign((size_t)cfg->n_layers, 0);
+  ctx->hint.assign((size_t)cfg->n_layers, 0);
   ctx->qslot.assign((size_t)cfg->n_layers, 0);
   *out = ctx;
   return DYNTS_OK;
@@ -419,6 +474,8 @@ int dynts_bind(dynts_ctx *ctx, uint16_t *K, uint16_t *V, float *S, int32_t *pos,
   ctx->paged = false; ctx->block_table = nullptr; ctx->free_stack = nullptr; ctx->free_top = nullptr;
   ctx->max_pages = ctx->n_pages = 0;
   ctx->pending.assign(ctx->pending.size(), 0);
+  ctx->hint.assign(ctx->hint.size(), 0);
+  ctx->spill_layer = -1;
   ctx->qslot.assign(ctx->qslot.size(), 0);
   ctx->bound = true;
   return DYNTS_OK;
@@ -466,6 +523,7 @@ int dynts_prefill(dynts_ctx *ctx, int32_t layer, const uint16_t *K0, const uint1
     hipLaunchKernelGGL((dynts::prefill_kernel<64>), grid, dim3(256), 0, st, p);
   }
   ctx->pending[layer] = 0;
+  if (ctx->spill_layer == layer) ctx->spill_layer = -1;
   return launch_status();
 }
 
@@ -501,6 +559,10 @@ int dynts_decode_attend(dynts_ctx *ctx, int32_t layer, const uint16_t *q, const 
   if (rc != DYNTS_OK) return rc;
   if (!q || !out) return DYNTS_ENULL;
   if (reinterpret_cast<uintptr_t>(q) % 16) return DYNTS_EINVAL;
+  if (ctx->pending[layer] == 2) {  // kept logits would lose their statistics to this call: apply them first
+    rc = apply_spill(ctx, layer, static_cast<hipStream_t>(stream));
+    if (rc != DYNTS_OK) return rc;
+  }
   rc = run_attend(ctx, layer, q, nullptr, nullptr, nullptr, active, out, lse, true, false, false,
                   static_cast<hipStream_t>(stream));
   if (rc == DYNTS_OK) ctx->pending[layer] = ctx->cfg.score_mode == DYNTS_SCORE_ACCUMULATE;
@@ -511,6 +573,7 @@ int dynts_update_scores(dynts_ctx *ctx, int32_t layer, void *stream) {
   int rc = check_call(ctx, layer);
   if (rc != DYNTS_OK) return rc;
   if (!ctx->pending[layer]) return DYNTS_OK;
+  if (ctx->pending[layer] == 2) return apply_spill(ctx, layer, static_cast<hipStream_t>(stream));
   rc = run_attend(ctx, layer, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, false, true, false,
                   static_cast<hipStream_t>(stream));
   if (rc == DYNTS_OK) ctx->pending[layer] = 0;
@@ -523,10 +586,8 @@ int dynts_decode_attend_update(dynts_ctx *ctx, int32_t layer, const uint16_t *q,
   if (rc != DYNTS_OK) return rc;
   if (!q || !out) return DYNTS_ENULL;
   if (reinterpret_cast<uintptr_t>(q) % 16) return DYNTS_EINVAL;
-  rc = run_attend(ctx, layer, q, nullptr, nullptr, nullptr, active, out, lse, true, ctx->pending[layer] != 0,
-                  false, static_cast<hipStream_t>(stream));
-  if (rc == DYNTS_OK) ctx->pending[layer] = ctx->cfg.score_mode == DYNTS_SCORE_ACCUMULATE;
-  return rc;
+  return fused_step(ctx, layer, q, nullptr, nullptr, nullptr, active, out, lse, false, static_cast<hipStream_t>(stream),
+                    nullptr);
 }
 
 int dynts_decode_step(dynts_ctx *ctx, int32_t layer, const uint16_t *q, const uint16_t *k_new,
@@ -539,10 +600,8 @@ int dynts_decode_step(dynts_ctx *ctx, int32_t layer, const uint16_t *q, const ui
   if (ext && !s_new) return DYNTS_ENULL;
   if ((reinterpret_cast<uintptr_t>(q) | reinterpret_cast<uintptr_t>(k_new) | reinterpret_cast<uintptr_t>(v_new)) % 16)
     return DYNTS_EINVAL;
-  rc = run_attend(ctx, layer, q, k_new, v_new, ext ? s_new : nullptr, active, out, lse, true,
-                  ctx->pending[layer] != 0, true, static_cast<hipStream_t>(stream));
-  if (rc == DYNTS_OK) ctx->pending[layer] = !ext;
-  return rc;
+  return fused_step(ctx, layer, q, k_new, v_new, ext ? s_new : nullptr, active, out, lse, true,
+                    static_cast<hipStream_t>(stream), nullptr);
 }
 
 int dynts_decode_step_static(dynts_ctx *ctx, int32_t layer, const uint16_t *q, const uint16_t *k_new,
@@ -574,10 +633,14 @@ int dynts_decode_step_static(dynts_ctx *ctx, int32_t layer, const uint16_t *q, c
   tr.seq_cnt = reinterpret_cast<uint32_t *>(base + kStaticCounters / 2);
   tr.part_o = reinterpret_cast<uint64_t *>(base + kStaticCounters);
   tr.part_ml = reinterpret_cast<uint64_t *>(base + kStaticCounters + part_o_bytes);
-  rc = run_attend(ctx, layer, q, k_new, v_new, ext ? s_new : nullptr, active, out, lse, true,
-                  ctx->pending[layer] != 0, true, st, &tr);
-  if (rc == DYNTS_OK) ctx->pending[layer] = !ext;
-  return rc;
+  return fused_step(ctx, layer, q, k_new, v_new, ext ? s_new : nullptr, active, out, lse, true, st, &tr);
+}
+
+int dynts_hint_trigger(dynts_ctx *ctx, int32_t layer) {
+  const int rc = check_call(ctx, layer);
+  if (rc != DYNTS_OK) return rc;
+  ctx->hint[layer] = 1;
+  return DYNTS_OK;
 }
 
 int dynts_select_evict(dynts_ctx *ctx, int32_t layer, const uint8_t *trigger, int32_t k_keep, int32_t *keep_idx,
@@ -802,6 +865,7 @@ int dynts_decode_loop(dynts_ctx *ctx, int32_t n_steps, const uint16_t *q, const 
     const float *sn = ext ? s_new + (size_t)i * c.batch * c.n_kv_heads : nullptr;
     for (int l = 0; l < c.n_layers; ++l) {
       const size_t sl = (size_t)i * c.n_layers + l;
+      if (evict_steps && evict_steps[i]) ctx->hint[l] = 1;  // the trigger below follows this step
       rc = dynts_decode_step(ctx, l, q + sl * q_layer, k_new + sl * kv_layer, v_new + sl * kv_layer, sn, act,
                              out + (size_t)i * out_step_stride + (size_t)l * q_layer, nullptr, stream);
       if (rc != DYNTS_OK) return rc;

@@ -88,11 +88,18 @@ class SideBySide:
         qd, kd, vd = q.to(dev).contiguous(), k.to(dev).contiguous(), v.to(dev).contiguous()
         sd = s.to(dev).contiguous() if s is not None else None
         ad = torch.from_numpy(active).to(dev) if active is not None else None
+        if self.mode.endswith("+hint"):
+            # announce the trigger that will follow this step (the oracle's rule, evaluated before the append), so that
+            # the step keeps its logits and the score update owed at the trigger is applied from them
+            o = self.o
+            act_b = np.ones(c.cfg.batch, bool) if active is None else active.astype(bool)
+            if (act_b & (o.seq_len - o.n_prompt + 1 >= o.budget + o.window + o.evict_every)).any():
+                B.dynts_hint_trigger(c.ctx, L)
         if self.mode == "unfused":
             B.dynts_append(c.ctx, L, kd, vd, sd, ad)
             B.dynts_decode_attend(c.ctx, L, qd, self.out, self.lse, ad)
             B.dynts_update_scores(c.ctx, L)
-        elif self.mode == "fused":
+        elif self.mode.startswith("fused"):
             B.dynts_append(c.ctx, L, kd, vd, sd, ad)
             B.dynts_decode_attend_update(c.ctx, L, qd, self.out, self.lse, ad)
         else:

@@ -40,7 +40,7 @@ def _check_pages(cache):
 
 
 @pytest.mark.parametrize("one_workgroup", [False, True])
-@pytest.mark.parametrize("mode", ["unfused", "fused", "step"])
+@pytest.mark.parametrize("mode", ["unfused", "fused", "step", "step+hint"])
 @pytest.mark.parametrize("d,Hq,Hkv", [(64, 8, 2), (128, 28, 4)])
 def test_trajectory_paged(B, mode, d, Hq, Hkv, one_workgroup):
     """Several pages per unit, ragged prompts, evictions that free pages, a sequence that finishes early.

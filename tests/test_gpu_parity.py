@@ -30,7 +30,7 @@ def _pair(B, Nb, Hq, Hkv, d, M_max, budget, window, E, mode, external=False, sca
     return SideBySide(B, cache, 0, o, mode), cap
 
 
-@pytest.mark.parametrize("mode", ["unfused", "fused", "step"])
+@pytest.mark.parametrize("mode", ["unfused", "fused", "step", "step+hint", "fused+hint"])
 @pytest.mark.parametrize("d,Hq,Hkv", [(64, 8, 2), (128, 28, 4), (128, 6, 6), (128, 16, 1)])
 def test_trajectory_small(B, mode, d, Hq, Hkv):
     """Several tiles, a ragged tail, ragged prompts, several evictions, a sequence that finishes early."""
@@ -54,14 +54,15 @@ def test_trajectory_small(B, mode, d, Hq, Hkv):
     assert int(sbs.c.seq_len[0, 1].item()) == sbs.o.seq_len[1]
 
 
+@pytest.mark.parametrize("hint", ["", "+hint"])
 @pytest.mark.parametrize("waves", [4, 8])
 @pytest.mark.parametrize("d,Hq,Hkv", [(64, 8, 2), (128, 28, 4)])
-def test_trajectory_single_workgroup(B, d, Hq, Hkv, waves):
+def test_trajectory_single_workgroup(B, d, Hq, Hkv, waves, hint):
     """One workgroup per (sequence, KV head), 4 or 8 waves: every wave walks a ragged range of slots behind its
     first tile, the launch shape of the large workloads, here at a size the oracle replays step by step."""
     rng = np.random.default_rng(500 + d + Hq)
     Nb, M_max, budget, window, E, T = 2, 41, 330, 23, 57, 560
-    sbs, cap = _pair(B, Nb, Hq, Hkv, d, M_max, budget, window, E, "step", launch_shape=(1, waves))
+    sbs, cap = _pair(B, Nb, Hq, Hkv, d, M_max, budget, window, E, "step" + hint, launch_shape=(1, waves))
     sbs.prefill(_bf16(rng, Nb, Hkv, M_max, d), _bf16(rng, Nb, Hkv, M_max, d), [41, 7])
     for t in range(1, T + 1):
         sbs.step(_bf16(rng, Nb, Hq, d, scale=1.5), _bf16(rng, Nb, Hkv, d), _bf16(rng, Nb, Hkv, d),
@@ -325,7 +326,8 @@ def test_long_cache_single_unit(B):
 @pytest.mark.parametrize("external", [False, True])
 def test_native_loop_equals_single_calls(B, external):
     """dynts_decode_loop over several layers (per-step input slabs, ragged activity, trigger steps, one output slab
-    per step) does exactly what the same calls issued one by one do: bit-identical caches and outputs."""
+    per step) does exactly what the same calls issued one by one do (trigger steps announced, as the loop announces
+    them): bit-identical caches and outputs."""
     rng = np.random.default_rng(21)
     dev = torch.device("cuda:0")
     L, Nb, Hq, Hkv, d = 3, 4, 8, 2, 64
@@ -360,6 +362,8 @@ def test_native_loop_equals_single_calls(B, external):
                         trigger=trig, out_step_stride=outs_a[0].numel())
     for t in range(T):
         for l in range(L):
+            if flags[t]:
+                B.dynts_hint_trigger(b_.ctx, l)   # as the loop does on its trigger steps
             B.dynts_decode_step(b_.ctx, l, q[t, l], k[t, l], v[t, l], outs_b[t, l], s_new=s[t] if external else None,
                                 active=act[t])
             if flags[t]:
