@@ -15,6 +15,12 @@ namespace dynts {
 
 constexpr int kCompactThreads = 256;
 constexpr int kCompactUnroll = 4;
+// A workgroup moves one column slice of this many bytes of every row: whole 128-byte lines, so that no line is
+// fetched by two workgroups (64-byte slices read 2.8 bytes per byte written on the 32-layer workload).
+#ifndef DYNTS_COMPACT_SLICE
+#define DYNTS_COMPACT_SLICE 128
+#endif
+constexpr int kCompactSliceBytes = DYNTS_COMPACT_SLICE;
 
 struct CompactParams {
   uint16_t *K, *V;          // [Nb][Hkv][cap][D]
@@ -29,15 +35,15 @@ struct CompactParams {
 
 __device__ __forceinline__ int clamp_slot(int v, int cap) { return v < 0 ? 0 : (v >= cap ? cap - 1 : v); }
 
-// grid (2 * kSlices + 2, Hkv, Nb): x < kSlices moves one 64-byte column slice of the K rows,
+// grid (2 * kSlices + 2, Hkv, Nb): x < kSlices moves one column slice of the K rows,
 // the next kSlices the same for V, the last two move S and pos.  Column slices are independent
 // copies, so the in-place argument above holds for each of them; splitting a row over several
 // workgroups shortens the chain of dependent round trips (index, row, barrier, store) that bounds
 // this kernel: a trigger usually moves a few hundred rows per unit.
 template <int D>
 __global__ __launch_bounds__(kCompactThreads) void compact_kernel(const CompactParams p) {
-  constexpr int kSlices = D * 2 / 64;               // 64-byte slices per row
-  constexpr int LPS = 4;                            // lanes per row slice (16 bytes each)
+  constexpr int kSlices = D * 2 / kCompactSliceBytes;   // column slices per row
+  constexpr int LPS = kCompactSliceBytes / 16;          // lanes per row slice (16 bytes each)
   constexpr int ROWS = kCompactThreads / LPS;       // rows per pass
   constexpr int TILE = ROWS * kCompactUnroll;       // destinations per barrier
   __shared__ int sh_first;
@@ -63,7 +69,7 @@ __global__ __launch_bounds__(kCompactThreads) void compact_kernel(const CompactP
   const int first = sh_first;
 
   if (what < 2 * kSlices) {
-    uint16_t *base = (what < kSlices ? p.K : p.V) + unit * (size_t)p.cap * D + 32 * (what % kSlices);
+    uint16_t *base = (what < kSlices ? p.K : p.V) + unit * (size_t)p.cap * D + (kCompactSliceBytes / 2) * (what % kSlices);
     const int r = tid / LPS, piece = tid % LPS;
     // Two tiles in flight: the rows of tile t+1 are requested before tile t is stored.  That is safe
     // because every source of tile t+1 lies at or beyond its own first destination, past all of

@@ -676,7 +676,7 @@ int dynts_compact(dynts_ctx *ctx, int32_t layer, const uint8_t *trigger, const i
   const LayerView lv = layer_view(ctx, layer);
   dynts::CompactParams p{lv.K, lv.V, lv.S, lv.pos, lv.seq_len, trigger, keep_idx, new_len,
                          c.n_kv_heads, c.capacity, keep_stride};
-  const dim3 grid(2 * (c.head_dim * 2 / 64) + 2, c.n_kv_heads, c.batch);
+  const dim3 grid(2 * (c.head_dim * 2 / dynts::kCompactSliceBytes) + 2, c.n_kv_heads, c.batch);
   hipStream_t st = static_cast<hipStream_t>(stream);
   if (ctx->paged) {
     const dynts::PagedView pv{lv.K, lv.V, lv.block_table, ctx->free_stack, ctx->free_top, ctx->max_pages, ctx->n_pages};

@@ -139,8 +139,8 @@ __global__ void paged_append_kernel(const AppendParams p, PagedView pv) {
 // grid (2 * kSlices + 2, Hkv, Nb), 256 threads.
 template <int D>
 __global__ __launch_bounds__(kCompactThreads) void paged_compact_kernel(const CompactParams p, PagedView pv) {
-  constexpr int kSlices = D * 2 / 64;
-  constexpr int LPS = 4;
+  constexpr int kSlices = D * 2 / kCompactSliceBytes;
+  constexpr int LPS = kCompactSliceBytes / 16;
   constexpr int ROWS = kCompactThreads / LPS;
   constexpr int TILE = ROWS * kCompactUnroll;
   __shared__ int sh_first;
@@ -165,7 +165,7 @@ __global__ __launch_bounds__(kCompactThreads) void paged_compact_kernel(const Co
   const int first = sh_first;
 
   if (what < 2 * kSlices) {
-    uint16_t *pool = (what < kSlices ? pv.K : pv.V) + 32 * (what % kSlices);
+    uint16_t *pool = (what < kSlices ? pv.K : pv.V) + (kCompactSliceBytes / 2) * (what % kSlices);
     const int r = tid / LPS, piece = tid % LPS;
     typedef uint32_t u32x4_t __attribute__((ext_vector_type(4)));
     for (int i0 = first; i0 < m; i0 += TILE) {
