@@ -35,6 +35,27 @@ struct CompactParams {
 
 __device__ __forceinline__ int clamp_slot(int v, int cap) { return v < 0 ? 0 : (v >= cap ? cap - 1 : v); }
 
+// First destination whose source differs.  keep_idx[i] == i holds on a prefix only, so the boundary is found by
+// cutting the range 256 ways at a time, every thread probing one position: two or three rounds of one load
+// each, where a bisection by one thread makes eleven dependent loads.  Called by all threads of the workgroup.
+__device__ __forceinline__ int first_moved(const int32_t *ku, int m) {
+  const int tid = threadIdx.x;
+  int lo = 0, hi = m;  // the boundary lies in [lo, hi]
+  while (lo < hi) {
+    const int step = (hi - lo + kCompactThreads - 1) / kCompactThreads;
+    const int idx = lo + tid * step;
+    const int c = __syncthreads_count(idx < hi && ku[idx] == idx);  // probes 0 .. c-1 hold, probe c does not
+    if (c == 0) {
+      hi = lo;
+    } else {
+      const int up = lo + c * step;
+      lo = lo + (c - 1) * step + 1;
+      hi = up < hi ? up : hi;
+    }
+  }
+  return lo;
+}
+
 // grid (2 * kSlices + 2, Hkv, Nb): x < kSlices moves one column slice of the K rows,
 // the next kSlices the same for V, the last two move S and pos.  Column slices are independent
 // copies, so the in-place argument above holds for each of them; splitting a row over several
@@ -46,7 +67,6 @@ __global__ __launch_bounds__(kCompactThreads) void compact_kernel(const CompactP
   constexpr int LPS = kCompactSliceBytes / 16;          // lanes per row slice (16 bytes each)
   constexpr int ROWS = kCompactThreads / LPS;       // rows per pass
   constexpr int TILE = ROWS * kCompactUnroll;       // destinations per barrier
-  __shared__ int sh_first;
   const int tid = threadIdx.x;
   const int what = blockIdx.x, h = blockIdx.y, b = blockIdx.z;
   if (p.trigger && !p.trigger[b]) return;
@@ -56,17 +76,7 @@ __global__ __launch_bounds__(kCompactThreads) void compact_kernel(const CompactP
   const size_t unit = (size_t)b * p.Hkv + h;
   const int32_t *ku = p.keep_idx + unit * (size_t)p.keep_stride;
 
-  // first destination whose source differs (keep_idx[i] == i is true on a prefix only)
-  if (tid == 0) {
-    int lo = 0, hi = m;
-    while (lo < hi) {
-      int mid = (lo + hi) >> 1;
-      if (ku[mid] == mid) lo = mid + 1; else hi = mid;
-    }
-    sh_first = lo;
-  }
-  __syncthreads();
-  const int first = sh_first;
+  const int first = first_moved(ku, m);
 
   if (what < 2 * kSlices) {
     uint16_t *base = (what < kSlices ? p.K : p.V) + unit * (size_t)p.cap * D + (kCompactSliceBytes / 2) * (what % kSlices);

@@ -143,7 +143,6 @@ __global__ __launch_bounds__(kCompactThreads) void paged_compact_kernel(const Co
   constexpr int LPS = kCompactSliceBytes / 16;
   constexpr int ROWS = kCompactThreads / LPS;
   constexpr int TILE = ROWS * kCompactUnroll;
-  __shared__ int sh_first;
   const int tid = threadIdx.x;
   const int what = blockIdx.x, h = blockIdx.y, b = blockIdx.z;
   if (p.trigger && !p.trigger[b]) return;
@@ -153,16 +152,7 @@ __global__ __launch_bounds__(kCompactThreads) void paged_compact_kernel(const Co
   const size_t unit = (size_t)b * p.Hkv + h;
   const int32_t *ku = p.keep_idx + unit * (size_t)p.keep_stride;
   const int32_t *tb = pv.block_table + unit * pv.max_pages;
-  if (tid == 0) {
-    int lo = 0, hi = m;
-    while (lo < hi) {
-      int mid = (lo + hi) >> 1;
-      if (ku[mid] == mid) lo = mid + 1; else hi = mid;
-    }
-    sh_first = lo;
-  }
-  __syncthreads();
-  const int first = sh_first;
+  const int first = first_moved(ku, m);
 
   if (what < 2 * kSlices) {
     uint16_t *pool = (what < kSlices ? pv.K : pv.V) + (kCompactSliceBytes / 2) * (what % kSlices);
