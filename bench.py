@@ -392,6 +392,7 @@ def run_gpu(args, wl):
                 whole_step_gbs=step_bytes / dt / 1e9, seq_steps_per_s=sum(act_counts) / dt,
                 evictions_timed=int(ft.sum()), first_timed_step=t + args.warmup + 1,
                 active_min=min(act_counts), active_max=max(act_counts), full_period=full_period,
+                page_order=getattr(cache, "page_order", None),
                 windows={"n": n_win, "steps_each": win, "ms_per_step_median": round(win_ms[len(win_ms) // 2], 5),
                          "ms_per_step_min": round(win_ms[0], 5), "ms_per_step_max": round(win_ms[-1], 5)})
 
@@ -634,7 +635,8 @@ def result_line(args, wl, r, cpu):
                                 "block scoring of %d queries per sequence on a steady-state cache" % args.score_block
                                 if getattr(args, "score_block", 0) else
                                 "whole decode from the prompt" if args.trajectory else
-                                "steady state, paged layout" if getattr(args, "paged", False) else "steady state",
+                                "steady state, paged layout (initial page order: %s)" % r.get("page_order")
+                                if getattr(args, "paged", False) else "steady state",
                                 r["active_min"], r["active_max"], wl.batch),
                    "first_timed_step": r["first_timed_step"], "evictions_in_window": r["evictions_timed"],
                    "sequence_steps_per_s": round(r["seq_steps_per_s"], 1), "timed_windows": r.get("windows"),

@@ -112,7 +112,12 @@ int dynts_bind(dynts_ctx *ctx, uint16_t *K, uint16_t *V, float *S, int32_t *pos,
  * any other sequence.  dynts_prefill expects the layer's units to hold no pages.  When the stack runs dry the
  * row is dropped and bit 2 (value 4) of the status word is latched; results are undefined from then on.
  * The pools must hold finite values before first use (zero-filled, say): rows beyond a sequence's length may be
- * read, with zero weight.  S, pos and the per-sequence arrays keep the dense layout.  Everything else behaves as after dynts_bind. */
+ * read, with zero weight.  S, pos and the per-sequence arrays keep the dense layout.  Everything else behaves as after dynts_bind.
+ * The ORDER of the ids in the initial stack is the caller's choice and decides where a unit's pages lie.  With ids in
+ * order, sequences that append in step get neighbouring pages round after round, so a unit's pages lie a fixed
+ * power-of-two stride apart: good for caches streamed from HBM, but a cache small enough to stay in the 256 MB
+ * memory-side cache then runs up to 25 % slower than with a shuffled stack (measured, 159 MB of K/V: 35 - 40 us per
+ * attend launch in order, 31.5 us shuffled, 30 us dense); beyond that size a shuffled stack costs 3 - 5 %. */
 int dynts_bind_paged(dynts_ctx *ctx, uint16_t *K_pool, uint16_t *V_pool, int32_t n_pages, int32_t *block_table,
                      int32_t max_pages, int32_t *free_stack, int32_t *free_top, float *S, int32_t *pos,
                      int32_t *seq_len, int32_t *next_pos, int32_t *n_prompt, void *workspace,

@@ -306,12 +306,16 @@ def dynts_predictor_pack(W, stream=None):
 PAGE_SLOTS = 64
 
 
+PAGED_SHUFFLE_BELOW_BYTES = 200 << 20
+
+
 class PagedCache:
     """The paged layout's buffers (page pools, block table, free stack) allocated with torch and bound.
     `K` and `V` give a dense [L][Nb][Hkv][cap][d] copy gathered through the block table (for inspection)."""
 
     def __init__(self, n_layers, batch, n_q_heads, n_kv_heads, head_dim, capacity, budget, window, evict_every,
-                 n_pages=None, softmax_scale=0.0, external_scores=False, device="cuda:0", launch_shape=None):
+                 n_pages=None, softmax_scale=0.0, external_scores=False, device="cuda:0", launch_shape=None,
+                 page_order="auto"):
         self.cfg = make_config(n_layers, batch, n_q_heads, n_kv_heads, head_dim, capacity, budget, window,
                                evict_every, softmax_scale,
                                DYNTS_SCORE_EXTERNAL if external_scores else DYNTS_SCORE_ACCUMULATE)
@@ -325,7 +329,20 @@ class PagedCache:
         self.K_pool = torch.zeros((self.n_pages, PAGE_SLOTS, d), dtype=torch.bfloat16, device=dev)
         self.V_pool = torch.zeros((self.n_pages, PAGE_SLOTS, d), dtype=torch.bfloat16, device=dev)
         self.block_table = torch.full((L, Nb, Hkv, self.max_pages), -1, dtype=torch.int32, device=dev)
-        self.free_stack = torch.arange(self.n_pages, dtype=torch.int32, device=dev)
+        # The order of the ids in the initial free stack decides where a unit's pages lie (see dynts_bind_paged in
+        # dynts.h): "sequential" (ids in order: units that append in step get neighbouring pages), "shuffled" (a
+        # fixed pseudo-random permutation), "auto" = shuffled when one layer's K/V fits the 256 MB memory-side cache.
+        if page_order == "auto":
+            kv_layer_bytes = 2 * Nb * Hkv * cap * d * 2
+            page_order = "shuffled" if kv_layer_bytes <= PAGED_SHUFFLE_BELOW_BYTES else "sequential"
+        if page_order == "shuffled":
+            gen = torch.Generator().manual_seed(0x5EED)
+            self.free_stack = torch.randperm(self.n_pages, generator=gen).to(torch.int32).to(dev)
+        elif page_order == "sequential":
+            self.free_stack = torch.arange(self.n_pages, dtype=torch.int32, device=dev)
+        else:
+            raise ValueError("page_order must be 'auto', 'sequential' or 'shuffled'")
+        self.page_order = page_order
         self.free_top = torch.full((1,), self.n_pages, dtype=torch.int32, device=dev)
         self.S = torch.zeros((L, Nb, Hkv, cap), dtype=torch.float32, device=dev)
         self.pos = torch.zeros((L, Nb, Hkv, cap), dtype=torch.int32, device=dev)
@@ -340,10 +357,11 @@ class PagedCache:
                          self.pos, self.seq_len, self.next_pos, self.n_prompt, self.workspace, self.status)
 
     @classmethod
-    def for_workload(cls, wl, device="cuda:0", n_layers=None, n_pages=None, launch_shape=None):
+    def for_workload(cls, wl, device="cuda:0", n_layers=None, n_pages=None, launch_shape=None, page_order="auto"):
         return cls(wl.n_layers if n_layers is None else n_layers, wl.batch, wl.n_q_heads, wl.n_kv_heads,
                    wl.head_dim, wl.capacity, wl.budget, wl.window, wl.evict_every, n_pages=n_pages,
-                   external_scores=wl.external_scores, device=device, launch_shape=launch_shape)
+                   external_scores=wl.external_scores, device=device, launch_shape=launch_shape,
+                   page_order=page_order)
 
     def _dense(self, pool):
         idx = self.block_table.clamp(min=0).long()                      # [L][Nb][Hkv][max_pages]
