@@ -374,7 +374,10 @@ def run_gpu(args, wl):
     # hold several: 5 in-stream windows of one period each, every one with exactly one trigger in it
     full_period = None
     if args.steps < 5 * E:
-        full_period = time_periods(B, cache, gen, wl, lengths, out, t_end + n_prof, dev, n_periods=5)
+        # (as many windows, up to 5, as end before the shortest sequence does: the batch stays full)
+        n_per = min(5, (int(lengths.min()) - (t_end + n_prof)) // E)
+        if n_per >= 1:
+            full_period = time_periods(B, cache, gen, wl, lengths, out, t_end + n_prof, dev, n_periods=n_per)
     stream = read_stream_rates(B, int(bytes_launch) // 16 * 16, dev)
     roofline = {"bound": "hbm", "kernel": "attend_kernel<%d,attend,pending,append>" % wl.head_dim,
                 "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
