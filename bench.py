@@ -497,6 +497,19 @@ def run_score_block(args, wl):
         rates.append(2048 * 256 * 4000 * 8 / (hev.elapsed_ms(0) * 1e-3))
     hev.close()
     exp_rate = max(rates[1:])
+    # the third: the kernels' own instruction mix without memory (16 MFMA + 16 x (fma, exp2, add) per wave and
+    # streamed 16-row tile), three waves per SIMD as the kernels run; time per tile and SIMD
+    hev = HipEvents(1)
+    mix_ns = {}
+    for what, name in ((1, "mfma_only"), (2, "vector_only"), (3, "both")):
+        best = None
+        for _ in range(3):
+            B.dynts_probe_issue_mix(768, 20000, what, sink, hev.pairs[0][0], hev.pairs[0][1])
+            torch.cuda.synchronize()
+            t = hev.elapsed_ms(0) * 1e6 / 20000 / 3
+            best = t if best is None or t < best else best
+        mix_ns[name] = round(best, 1)
+    hev.close()
     units, R, d = wl.batch * wl.n_kv_heads, T * wl.group, wl.head_dim
     # the contraction the method defines: every query row against the cached slots and its visible block keys
     flops = units * 2.0 * d * (R * n0 + wl.group * T * (T + 1) / 2)
@@ -512,7 +525,14 @@ def run_score_block(args, wl):
                                  "peak_exp2_per_s": round(exp_rate / 1e12, 2), "unit": "T/s, measured by "
                                  "dynts_probe_exp_rate in this run",
                                  "achieved_exp2_per_s": round(units * (2.0 * R * n0) / (ev_ms * 1e-3) / 1e12, 2),
-                                 "frac": round(units * (2.0 * R * n0) / (ev_ms * 1e-3) / exp_rate, 4)}}
+                                 "frac": round(units * (2.0 * R * n0) / (ev_ms * 1e-3) / exp_rate, 4)},
+                "issue_bound": {"kind": "the kernels' instruction mix with no memory access: 16 MFMA + 16 x (fma, exp2, "
+                                        "add) per wave and streamed 16-row tile, 3 waves per SIMD (dynts_probe_issue_mix "
+                                        "in this run)",
+                                "ns_per_tile_and_simd": mix_ns,
+                                "wave_tiles_per_call": executed / (16 * 16384.0),
+                                "floor_ms_per_call": round(executed / (16 * 16384.0) / 1024 * mix_ns["both"] * 1e-6, 4),
+                                "frac": round(executed / (16 * 16384.0) / 1024 * mix_ns["both"] * 1e-6 / ev_ms, 4)}}
     return dict(value=args.steps / dt, ms_per_step=dt / args.steps * 1e3, roofline=roofline,
                 whole_step_gbs=0.0, seq_steps_per_s=args.steps * wl.batch / dt, evictions_timed=0,
                 first_timed_step=0, active_min=wl.batch, active_max=wl.batch)

@@ -313,6 +313,15 @@ int dynts_probe_read_stream(const void *buf, size_t bytes, int32_t n_workgroups,
  * that cannot occur.  start/stop: hipEvent_t handles attached to the dispatch, or both NULL. */
 int dynts_probe_exp_rate(int32_t n_workgroups, int32_t iters, float *sink, void *start, void *stop, void *stream);
 
+/* Measurement aid, not part of the method: the instruction mix of dynts_score_block's kernels with no memory
+ * access.  Every wave of n_workgroups x 256 lanes runs iters rounds of what one streamed 16-row tile costs it
+ * there: what & 1: 16 bf16 MFMAs (16x16x32) on four independent accumulators; what & 2: 16 x (multiply-add, 2^x,
+ * add) on independent registers; what = 3: both, interleaved by the compiler as in the kernels.  The time per
+ * round and SIMD is the floor of a tile that instruction issue and the two pipes set (Eq. attn-score's softmax
+ * needs the three vector instructions per logit).  sink, start/stop as for dynts_probe_exp_rate. */
+int dynts_probe_issue_mix(int32_t n_workgroups, int32_t iters, int32_t what, float *sink, void *start, void *stop,
+                          void *stream);
+
 #ifdef __cplusplus
 }
 #endif

@@ -25,7 +25,7 @@ EXPORTS = [
     "dynts_score_block_scratch_bytes", "dynts_score_block",
     "dynts_predict_scratch_bytes", "dynts_predict_scores", "dynts_predictor_pack", "dynts_bind_paged",
     "dynts_set_launch_shape", "dynts_ctx_workspace_bytes",
-    "dynts_decode_step_static", "dynts_probe_exp_rate", "dynts_hint_trigger",
+    "dynts_decode_step_static", "dynts_probe_exp_rate", "dynts_probe_issue_mix", "dynts_hint_trigger",
 ]
 
 
@@ -86,6 +86,7 @@ def _load():
     lib.dynts_predict_scores.argtypes = [C.POINTER(dynts_predictor), vp, i32, vp, i32, vp, sz, vp, vp, vp]
     lib.dynts_probe_read_stream.argtypes = [vp, sz, i32, C.c_uint32, vp, vp, vp, vp]
     lib.dynts_probe_exp_rate.argtypes = [i32, i32, vp, vp, vp, vp]
+    lib.dynts_probe_issue_mix.argtypes = [i32, i32, i32, vp, vp, vp, vp]
     for name in EXPORTS:
         getattr(lib, name)
     return lib
@@ -417,6 +418,12 @@ def dynts_probe_exp_rate(n_workgroups, iters, sink, start=None, stop=None, strea
     """sink: device float tensor of >= 1 element."""
     _check(lib.dynts_probe_exp_rate(n_workgroups, iters, sink.data_ptr(), start, stop, _stream(stream)),
            "dynts_probe_exp_rate")
+
+
+def dynts_probe_issue_mix(n_workgroups, iters, what, sink, start=None, stop=None, stream=None):
+    """what: 1 = the MFMAs of a block-scoring tile, 2 = its vector instructions, 3 = both; sink: device float tensor."""
+    _check(lib.dynts_probe_issue_mix(n_workgroups, iters, what, sink.data_ptr(), start, stop, _stream(stream)),
+           "dynts_probe_issue_mix")
 
 
 class Cache:

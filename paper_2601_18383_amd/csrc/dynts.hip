@@ -846,6 +846,21 @@ int dynts_probe_exp_rate(int32_t n_workgroups, int32_t iters, float *sink, void 
   return launch_status();
 }
 
+int dynts_probe_issue_mix(int32_t n_workgroups, int32_t iters, int32_t what, float *sink, void *start, void *stop,
+                          void *stream) {
+  if (!sink) return DYNTS_ENULL;
+  if (n_workgroups <= 0 || n_workgroups > (1 << 20) || iters <= 0 || what < 1 || what > 3) return DYNTS_EINVAL;
+  if ((start == nullptr) != (stop == nullptr)) return DYNTS_EINVAL;
+  const dim3 grid(n_workgroups), block(dynts::kProbeThreads);
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  hipEvent_t e0 = static_cast<hipEvent_t>(start), e1 = static_cast<hipEvent_t>(stop);
+  const float c = 0.1f, L = -3.f, magic = -12345.678f;
+  if (what == 1) hipExtLaunchKernelGGL(dynts::issue_mix_kernel<1>, grid, block, 0, st, e0, e1, 0, iters, c, L, magic, sink);
+  else if (what == 2) hipExtLaunchKernelGGL(dynts::issue_mix_kernel<2>, grid, block, 0, st, e0, e1, 0, iters, c, L, magic, sink);
+  else hipExtLaunchKernelGGL(dynts::issue_mix_kernel<3>, grid, block, 0, st, e0, e1, 0, iters, c, L, magic, sink);
+  return launch_status();
+}
+
 int dynts_decode_loop(dynts_ctx *ctx, int32_t n_steps, const uint16_t *q, const uint16_t *k_new,
                       const uint16_t *v_new, const float *s_new, const uint8_t *active, const uint8_t *evict_steps,
                       const uint8_t *trigger, float *out, size_t out_step_stride, int32_t *keep_idx,

@@ -333,22 +333,32 @@ __global__ __launch_bounds__(kSbWaves * 64) void score_block_colsum_kernel(const
 #pragma unroll
   for (int kt = 0; kt < kSbTiles; ++kt) sum[kt] = f32x4{0.f, 0.f, 0.f, 0.f};
 
-  // streamed: the R query rows, 32 per chunk through LDS.  A row beyond the last repeats the last
-  // row's data and gets L = +inf, so it contributes 2^(-inf) = 0.
+  // streamed: the R query rows, 32 per chunk through LDS, and with them their log2 denominators (one float
+  // per row, fetched by the first 32 threads and parked behind the rows: a load of its own inside the
+  // multiply loop would make every chunk wait for all outstanding loads).  A row beyond the last repeats the
+  // last row's data and gets L = +inf, so it contributes 2^(-inf) = 0.
+  __shared__ float ldsL[2][St::kChunk];
   const int st_piece = tid % St::PIECES;
   QueryWalk w[St::NL];
 #pragma unroll
   for (int k = 0; k < St::NL; ++k) w[k].init(tid / St::PIECES + St::RPP * k, St::kChunk, p.G, p.Hq, D);
   const uint32_t last_off = (uint32_t)(p.T - 1) * w[0].stride_i + (uint32_t)(p.G - 1) * w[0].stride_g;
   u32x4 stage[St::NL];
+  float stageL = INFINITY;
+  bool stageL_valid = false;
+  int l_row = tid & (St::kChunk - 1);  // the row whose L this thread fetches next (threads 0..31 park it)
 #define DYNTS_SB_FETCH()                                                                               \
   _Pragma("unroll") for (int k = 0; k < St::NL; ++k) {                                                 \
     stage[k] = *reinterpret_cast<const u32x4 *>(Qb + (w[k].r < R ? w[k].off : last_off) + 16 * st_piece); \
     w[k].advance(p.G);                                                                                 \
-  }
-#define DYNTS_SB_PARK(buf_)                                                                            \
+  }                                                                                                    \
+  stageL = Lb[l_row < R ? l_row : R - 1];                                                              \
+  stageL_valid = l_row < R;                                                                            \
+  l_row += St::kChunk;
+#define DYNTS_SB_PARK(b_)                                                                              \
   _Pragma("unroll") for (int k = 0; k < St::NL; ++k)                                                   \
-      *reinterpret_cast<u32x4 *>((buf_) + (tid / St::PIECES + St::RPP * k) * St::LROW + 16 * st_piece) = stage[k];
+      *reinterpret_cast<u32x4 *>(lds[b_] + (tid / St::PIECES + St::RPP * k) * St::LROW + 16 * st_piece) = stage[k]; \
+  if (tid < St::kChunk) ldsL[b_][tid] = stageL_valid ? stageL : INFINITY;
 
   // The tiles are software-pipelined: the MFMAs of tile t+1 (independent accumulators, so they issue
   // back to back) stand next to the exponentials and sums of tile t, so that the scheduler has
@@ -368,35 +378,34 @@ __global__ __launch_bounds__(kSbWaves * 64) void score_block_colsum_kernel(const
 
   const int n_chunks = (R + St::kChunk - 1) / St::kChunk;
   DYNTS_SB_FETCH()
-  DYNTS_SB_PARK(lds[0])
+  DYNTS_SB_PARK(0)
   if (n_chunks > 1) { DYNTS_SB_FETCH() }
-  float La = r16 < R ? Lb[r16] : INFINITY;  // log2 denominator of this lane's query column, even tile
-  float Lq = 16 + r16 < R ? Lb[16 + r16] : INFINITY;  // ... odd tile of the chunk
   f32x4 acc_a[kSbTiles], acc_b[kSbTiles];
   __syncthreads();
+  float La = ldsL[0][r16], Lq = ldsL[0][16 + r16];  // log2 denominators of this lane's query column, even / odd tile
   if (has_keys) DYNTS_SB_MM(acc_a, lds[0], 0)
   for (int ch = 0; ch < n_chunks; ++ch) {
     const char *buf = lds[ch & 1];
-    const int rn = (ch + 1) * St::kChunk + r16;
-    const float La_n = rn < R ? Lb[rn] : INFINITY;
-    const float Lq_n = rn + 16 < R ? Lb[rn + 16] : INFINITY;
     if (has_keys) {
       DYNTS_SB_MM(acc_b, buf, 1)
       DYNTS_SB_SUM(acc_a, La)
     }
-    if (ch + 1 < n_chunks) { DYNTS_SB_PARK(lds[(ch + 1) & 1]) }
+    if (ch + 1 < n_chunks) { DYNTS_SB_PARK((ch + 1) & 1) }
     if (ch + 2 < n_chunks) { DYNTS_SB_FETCH() }
     __syncthreads();
+    const float Lq_cur = Lq;
+    if (ch + 1 < n_chunks) {
+      La = ldsL[(ch + 1) & 1][r16];
+      Lq = ldsL[(ch + 1) & 1][16 + r16];
+    }
     if (has_keys) {
       if (ch + 1 < n_chunks) {
         DYNTS_SB_MM(acc_a, lds[(ch + 1) & 1], 0)
-        DYNTS_SB_SUM(acc_b, Lq)
+        DYNTS_SB_SUM(acc_b, Lq_cur)
       } else {
-        DYNTS_SB_SUM(acc_b, Lq)
+        DYNTS_SB_SUM(acc_b, Lq_cur)
       }
     }
-    La = La_n;
-    Lq = Lq_n;
   }
 #undef DYNTS_SB_MM
 #undef DYNTS_SB_SUM

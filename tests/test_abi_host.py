@@ -144,6 +144,14 @@ def test_argument_checks_of_the_wider_entry_points(B):
     assert B.lib.dynts_probe_read_stream(None, 1024, 4, 0, one, None, None, None) == B.DYNTS_ENULL
     assert B.lib.dynts_probe_read_stream(one, 1000, 4, 0, one, None, None, None) == B.DYNTS_EINVAL
     assert B.lib.dynts_probe_read_stream(one, 1024, 0, 0, one, None, None, None) == B.DYNTS_EINVAL
+    # the other two measurement aids
+    assert B.lib.dynts_probe_exp_rate(4, 10, None, None, None, None) == B.DYNTS_ENULL
+    assert B.lib.dynts_probe_exp_rate(0, 10, one, None, None, None) == B.DYNTS_EINVAL
+    assert B.lib.dynts_probe_issue_mix(4, 10, 3, None, None, None, None) == B.DYNTS_ENULL
+    for what in (0, 4, -1):
+        assert B.lib.dynts_probe_issue_mix(4, 10, what, one, None, None, None) == B.DYNTS_EINVAL
+    assert B.lib.dynts_probe_issue_mix(0, 10, 3, one, None, None, None) == B.DYNTS_EINVAL
+    assert B.lib.dynts_probe_issue_mix(4, 0, 3, one, None, None, None) == B.DYNTS_EINVAL
 
 
 def test_missing_library_is_an_import_error(monkeypatch, tmp_path):
