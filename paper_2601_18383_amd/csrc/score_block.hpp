@@ -158,7 +158,9 @@ __global__ __launch_bounds__(kSbWaves * 64) void score_block_stats_kernel(const 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int r16 = lane & 15, kg = lane >> 4;
   const int row0 = blk * kSbRowsPerWg + wave * kSbRowsPerWave;
-  const bool has_rows = row0 < R;  // a wave without rows still helps staging and meets the barriers
+  // (the same in every lane of a wave, and told so to the compiler; a wave without rows still helps staging and
+  // meets the barriers)
+  const bool has_rows = __builtin_amdgcn_readfirstlane((int)(row0 < R)) != 0;
   int n = p.seq_len[b];
   n = n < 0 ? 0 : (n > p.cap ? p.cap : n);
   const char *Qb = reinterpret_cast<const char *>(p.q_blk + ((size_t)b * p.T * p.Hq + (size_t)h * p.G) * D);
@@ -185,13 +187,23 @@ __global__ __launch_bounds__(kSbWaves * 64) void score_block_stats_kernel(const 
     l[qt] = 0.f;
   }
 
-  // one streamed tile: keys (4 kg + i) x query column r16, folded into (m, l).  MASKED: keys whose
-  // index key0 + 4 kg + i is not below lim[qt] do not exist for this query column.
-#define DYNTS_SB_FOLD(kf_, MASKED, key0_, lim_)                                                        \
-  _Pragma("unroll") for (int qt = 0; qt < kSbTiles; ++qt) {                                            \
-    f32x4 acc = {0.f, 0.f, 0.f, 0.f};                                                                  \
+  // One streamed tile in two parts, so that the loop below can put the MFMAs of the NEXT tile (four independent
+  // accumulators, issued back to back) beside the vector work of the current one:
+  //   MM:   logits of keys (4 kg + i) x query column r16 for the wave's four query tiles;
+  //   FOLD: fold them into (m, l).  MASKED: keys whose index key0 + 4 kg + i is not below lim[qt] do not exist
+  //         for this query column.
+#define DYNTS_SB_MM(acc_, buf_, tt_)                                                                   \
+  {                                                                                                    \
+    bf16x8 kf[KS];                                                                                     \
+    lds_row_frags<D>(kf, buf_, 16 * (tt_) + r16, kg);                                                  \
+    _Pragma("unroll") for (int qt = 0; qt < kSbTiles; ++qt) acc_[qt] = f32x4{0.f, 0.f, 0.f, 0.f};      \
     _Pragma("unroll") for (int ks = 0; ks < KS; ++ks)                                                  \
-        acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kf_[ks], qf[qt][ks], acc, 0, 0, 0);              \
+      _Pragma("unroll") for (int qt = 0; qt < kSbTiles; ++qt)                                          \
+          acc_[qt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kf[ks], qf[qt][ks], acc_[qt], 0, 0, 0);   \
+  }
+#define DYNTS_SB_FOLD(acc_, MASKED, key0_, lim_)                                                       \
+  _Pragma("unroll") for (int qt = 0; qt < kSbTiles; ++qt) {                                            \
+    f32x4 acc = acc_[qt];                                                                              \
     if (MASKED) {                                                                                      \
       _Pragma("unroll") for (int i = 0; i < 4; ++i)                                                    \
           if ((key0_) + 4 * kg + i >= lim_[qt]) acc[i] = -INFINITY;                                    \
@@ -222,7 +234,7 @@ __global__ __launch_bounds__(kSbWaves * 64) void score_block_stats_kernel(const 
 #define DYNTS_SB_PARK(buf_)                                                                            \
   _Pragma("unroll") for (int k = 0; k < St::NL; ++k)                                                   \
       *reinterpret_cast<u32x4 *>((buf_) + (st_row + St::RPP * k) * St::LROW + 16 * st_piece) = stage[k];
-#define DYNTS_SB_STREAM(src_, pitch_, rows_, lim_, CAUSAL_)                                                    \
+#define DYNTS_SB_STREAM(src_, pitch_, rows_, lim_, CAUSAL_)                                            \
   {                                                                                                    \
     const int n_chunks = ((rows_) + St::kChunk - 1) / St::kChunk;                                      \
     if (n_chunks > 0) {                                                                                \
@@ -230,27 +242,29 @@ __global__ __launch_bounds__(kSbWaves * 64) void score_block_stats_kernel(const 
       DYNTS_SB_PARK(lds[0])                                                                            \
       if (n_chunks > 1) { DYNTS_SB_FETCH(src_, pitch_, rows_, 1) }                                     \
       __syncthreads();                                                                                 \
-      for (int ch = 0; ch < n_chunks; ++ch) {                                                          \
-        const char *buf = lds[ch & 1];                                                                 \
+      f32x4 acc_a[kSbTiles], acc_b[kSbTiles];                                                          \
+      if (has_rows) DYNTS_SB_MM(acc_a, lds[0], 0)                                                      \
+      for (int ch = 0; ch + 1 < n_chunks; ++ch) { /* whole chunks: no key is masked unless CAUSAL_ */  \
+        const int nb = (ch + 1) & 1;                                                                   \
         if (has_rows) {                                                                                \
-          if ((CAUSAL_) || (ch + 1) * St::kChunk > (rows_)) { /* uniform: some keys are masked */      \
-            _Pragma("unroll") for (int tt = 0; tt < 2; ++tt) {                                         \
-              bf16x8 kf[KS];                                                                           \
-              lds_row_frags<D>(kf, buf, 16 * tt + r16, kg);                                            \
-              DYNTS_SB_FOLD(kf, true, ch * St::kChunk + 16 * tt, lim_)                                 \
-            }                                                                                          \
-          } else {                                                                                     \
-            _Pragma("unroll") for (int tt = 0; tt < 2; ++tt) {                                         \
-              bf16x8 kf[KS];                                                                           \
-              lds_row_frags<D>(kf, buf, 16 * tt + r16, kg);                                            \
-              DYNTS_SB_FOLD(kf, false, 0, lim_)                                                        \
-            }                                                                                          \
-          }                                                                                            \
+          DYNTS_SB_MM(acc_b, lds[ch & 1], 1)                                                           \
+          DYNTS_SB_FOLD(acc_a, CAUSAL_, ch * St::kChunk, lim_)                                         \
         }                                                                                              \
-        if (ch + 1 < n_chunks) { DYNTS_SB_PARK(lds[(ch + 1) & 1]) }                                    \
+        DYNTS_SB_PARK(lds[nb])                                                                         \
         if (ch + 2 < n_chunks) { DYNTS_SB_FETCH(src_, pitch_, rows_, ch + 2) }                         \
         __syncthreads();                                                                               \
+        if (has_rows) {                                                                                \
+          DYNTS_SB_MM(acc_a, lds[nb], 0)                                                               \
+          DYNTS_SB_FOLD(acc_b, CAUSAL_, ch * St::kChunk + 16, lim_)                                    \
+        }                                                                                              \
       }                                                                                                \
+      if (has_rows) { /* the last chunk may be partial: masked */                                      \
+        const int lc = n_chunks - 1;                                                                   \
+        DYNTS_SB_MM(acc_b, lds[lc & 1], 1)                                                             \
+        DYNTS_SB_FOLD(acc_a, true, lc * St::kChunk, lim_)                                              \
+        DYNTS_SB_FOLD(acc_b, true, lc * St::kChunk + 16, lim_)                                         \
+      }                                                                                                \
+      __syncthreads(); /* the buffers are filled again by the next stream */                           \
     }                                                                                                  \
   }
 
@@ -275,6 +289,7 @@ __global__ __launch_bounds__(kSbWaves * 64) void score_block_stats_kernel(const 
 #undef DYNTS_SB_PARK
 #undef DYNTS_SB_FETCH
 #undef DYNTS_SB_FOLD
+#undef DYNTS_SB_MM
   if (!has_rows) return;
 
   // merge the four lane groups of every query column, write L = c * m + log2(l)
@@ -316,7 +331,8 @@ __global__ __launch_bounds__(kSbWaves * 64) void score_block_colsum_kernel(const
   // uniform over the workgroup: nothing of this block is wanted
   if (blk * kSbRowsPerWg >= n || (blk + 1) * kSbRowsPerWg <= first) return;
   const int key0 = blk * kSbRowsPerWg + wave * kSbRowsPerWave;
-  const bool has_keys = key0 < n && key0 + kSbRowsPerWave > first;  // else: staging and barriers only
+  // (the same in every lane of a wave, and told so to the compiler: a plain branch instead of lane masks)
+  const bool has_keys = __builtin_amdgcn_readfirstlane((int)(key0 < n && key0 + kSbRowsPerWave > first)) != 0;  // else: staging and barriers only
   const char *Qb = reinterpret_cast<const char *>(p.q_blk + ((size_t)b * p.T * p.Hq + (size_t)h * p.G) * D);
   const float *Lb = p.stats + (size_t)unit * (size_t)p.Rpad;
   const float c = p.scale_log2;
@@ -383,29 +399,30 @@ __global__ __launch_bounds__(kSbWaves * 64) void score_block_colsum_kernel(const
   f32x4 acc_a[kSbTiles], acc_b[kSbTiles];
   __syncthreads();
   float La = ldsL[0][r16], Lq = ldsL[0][16 + r16];  // log2 denominators of this lane's query column, even / odd tile
+  // (the last chunk stands behind the loop: every iteration inside has the same shape, so no value has two
+  // homes at the loop's end)
   if (has_keys) DYNTS_SB_MM(acc_a, lds[0], 0)
-  for (int ch = 0; ch < n_chunks; ++ch) {
-    const char *buf = lds[ch & 1];
+  for (int ch = 0; ch + 1 < n_chunks; ++ch) {
+    const int nb = (ch + 1) & 1;
     if (has_keys) {
-      DYNTS_SB_MM(acc_b, buf, 1)
+      DYNTS_SB_MM(acc_b, lds[ch & 1], 1)
       DYNTS_SB_SUM(acc_a, La)
     }
-    if (ch + 1 < n_chunks) { DYNTS_SB_PARK((ch + 1) & 1) }
+    DYNTS_SB_PARK(nb)
     if (ch + 2 < n_chunks) { DYNTS_SB_FETCH() }
     __syncthreads();
     const float Lq_cur = Lq;
-    if (ch + 1 < n_chunks) {
-      La = ldsL[(ch + 1) & 1][r16];
-      Lq = ldsL[(ch + 1) & 1][16 + r16];
-    }
+    La = ldsL[nb][r16];
+    Lq = ldsL[nb][16 + r16];
     if (has_keys) {
-      if (ch + 1 < n_chunks) {
-        DYNTS_SB_MM(acc_a, lds[(ch + 1) & 1], 0)
-        DYNTS_SB_SUM(acc_b, Lq_cur)
-      } else {
-        DYNTS_SB_SUM(acc_b, Lq_cur)
-      }
+      DYNTS_SB_MM(acc_a, lds[nb], 0)
+      DYNTS_SB_SUM(acc_b, Lq_cur)
     }
+  }
+  if (has_keys) {
+    DYNTS_SB_MM(acc_b, lds[(n_chunks - 1) & 1], 1)
+    DYNTS_SB_SUM(acc_a, La)
+    DYNTS_SB_SUM(acc_b, Lq)
   }
 #undef DYNTS_SB_MM
 #undef DYNTS_SB_SUM
