@@ -49,7 +49,10 @@ def test_trajectory_paged(B, mode, d, Hq, Hkv, one_workgroup):
     rng = np.random.default_rng(300 + d + Hq)
     Nb, M_max, budget, window, E, T = 3, 37, 150, 19, 91, 420
     cap = M_max + budget + window + E
-    cache = B.PagedCache(1, Nb, Hq, Hkv, d, cap, budget, window, E, launch_shape=(1, 8) if one_workgroup else None)
+    # (both initial page orders are exercised: ids in order with the single-workgroup shape, shuffled otherwise)
+    cache = B.PagedCache(1, Nb, Hq, Hkv, d, cap, budget, window, E, launch_shape=(1, 8) if one_workgroup else None,
+                         page_order="sequential" if one_workgroup else "shuffled")
+    assert sorted(cache.free_stack.tolist()) == list(range(cache.n_pages))
     o = orc.OracleLayer(Nb, Hq, Hkv, d, cap, budget, window, E)
     sbs = SideBySide(B, cache, 0, o, mode)
     sbs.prefill(_bf16(rng, Nb, Hkv, M_max, d), _bf16(rng, Nb, Hkv, M_max, d), [37, 5, 20])
