@@ -88,7 +88,10 @@ class SideBySide:
         qd, kd, vd = q.to(dev).contiguous(), k.to(dev).contiguous(), v.to(dev).contiguous()
         sd = s.to(dev).contiguous() if s is not None else None
         ad = torch.from_numpy(active).to(dev) if active is not None else None
-        if self.mode.endswith("+hint"):
+        if self.mode.endswith("+hintall"):
+            # a hint before every step: mostly no trigger follows, and the kept logits are applied by the next step
+            B.dynts_hint_trigger(c.ctx, L)
+        elif self.mode.endswith("+hint"):
             # announce the trigger that will follow this step (the oracle's rule, evaluated before the append), so that
             # the step keeps its logits and the score update owed at the trigger is applied from them
             o = self.o

@@ -30,7 +30,7 @@ def _pair(B, Nb, Hq, Hkv, d, M_max, budget, window, E, mode, external=False, sca
     return SideBySide(B, cache, 0, o, mode), cap
 
 
-@pytest.mark.parametrize("mode", ["unfused", "fused", "step", "step+hint", "fused+hint"])
+@pytest.mark.parametrize("mode", ["unfused", "fused", "step", "step+hint", "fused+hint", "step+hintall"])
 @pytest.mark.parametrize("d,Hq,Hkv", [(64, 8, 2), (128, 28, 4), (128, 6, 6), (128, 16, 1)])
 def test_trajectory_small(B, mode, d, Hq, Hkv):
     """Several tiles, a ragged tail, ragged prompts, several evictions, a sequence that finishes early."""
